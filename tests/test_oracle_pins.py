@@ -1,0 +1,393 @@
+"""Pins for the CPU oracle: each part is checked against something other than itself
+(published known answers, closed forms, brute force with dense matrices, a library routine,
+finite differences, invariants of the SET prune/regrow cycle)."""
+import os
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+import scipy.special
+
+from paper_2102_01732_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def make_layer(orc, n_in, n_out, nnz, act_kind=1, parity=0, alpha=0.6, seed=5, layer_id=0, limit=0.5,
+               lr=0.01, mu=0.9, prune_mode=0):
+    return orc.OracleLayer(n_in, n_out, nnz, act_kind, parity, alpha, limit, lr, mu, 0.0, seed, layer_id,
+                           prune_mode)
+
+
+# ---------------------------------------------------------------------------- Philox (Salmon et al.)
+def test_philox_known_answers(oracle):
+    n = 0
+    for line in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        v = [int(t, 16) for t in line.split()]
+        out = oracle.philox(v[0:4], v[4:6])
+        assert [int(x) for x in out] == v[6:10]
+        n += 1
+    assert n == 3
+
+
+def test_weight_values_range_and_law(oracle):
+    pos = np.arange(200000, dtype=np.uint64) * np.uint64(7919)
+    w = oracle.weight_values(11, 3, 0, pos, 0.25)
+    assert w.dtype == np.float32
+    assert np.all(np.abs(w) < 0.25) and np.all(w != 0)
+    # uniform on (-limit, limit): mean 0, variance limit^2/3, flat histogram
+    assert abs(w.mean()) < 4 * 0.25 / np.sqrt(3 * w.size)
+    assert abs(w.var() - 0.25 ** 2 / 3) < 2e-4
+    hist, _ = np.histogram(w, bins=20, range=(-0.25, 0.25))
+    chi2 = ((hist - w.size / 20) ** 2 / (w.size / 20)).sum()
+    assert chi2 < 60          # 19 dof, p ~ 1e-6
+    # a different generation / layer gives a different stream; the same arguments the same values
+    assert np.array_equal(w, oracle.weight_values(11, 3, 0, pos, 0.25))
+    assert not np.array_equal(w, oracle.weight_values(11, 3, 1, pos, 0.25))
+    assert not np.array_equal(w, oracle.weight_values(11, 4, 0, pos, 0.25))
+    # grid of odd multiples of 2^-23 times the limit
+    q = w.astype(np.float64) / 0.25 * 2 ** 23
+    assert np.all(q == np.round(q)) and np.all(np.round(q).astype(np.int64) % 2 != 0)
+
+
+# ---------------------------------------------------------------------------- nnz of an ER layer
+def test_nnz_closed_form_and_paper_parameter_counts(oracle):
+    f = oracle.nnz_from_epsilon
+    # extreme-scale table: parameters = epsilon * sum(n_in + n_out) (stated there in millions)
+    assert 10 * ((65536 + 500000) + (500000 + 500000) + (500000 + 2)) == 20655380       # "20.6 M"
+    assert abs(5 * ((65536 + 2500000) + 2 * 2500000 + 2500002) / 1e6 - 50.3) < 0.05     # "50.3 M"
+    assert abs(5 * ((65536 + 5000000) + 2 * 5000000 + 5000002) / 1e6 - 100.3) < 0.05    # "100.3 M"
+    assert f(65536, 500000, 10) == 5655360 and f(500000, 500000, 10) == 10000000
+    # cap at the matrix size: narrow output layers are fully dense
+    assert f(500000, 2, 10) == 1000000 and f(400, 2, 10) == 800 and f(1000, 10, 20) == 10000
+    # CIFAR10-shaped net: 381 440 against the results table's start counts 381 758 / 381 425 / 380 318
+    dims = (3072, 4000, 1000, 4000, 10)
+    total = sum(f(dims[i], dims[i + 1], 20) for i in range(4))
+    assert total == 381440 and abs(total - 381425) / 381425 < 1e-3
+    # FashionMNIST-shaped: 125 680 against 126 302 / 125 901
+    dims = (784, 1000, 1000, 1000, 10)
+    total = sum(f(dims[i], dims[i + 1], 20) for i in range(4))
+    assert total == 125680 and abs(total - 125901) / 125901 < 5e-3
+    # Madelon-shaped: the table prints 19 000 for the three sparse layers
+    assert f(500, 400, 10) + f(400, 100, 10) + f(100, 400, 10) == 19000
+    # the workload module (used by the GPU side) agrees
+    for (a, b, e) in [(500, 400, 10), (400, 2, 10), (65536, 1000000, 10), (262144, 262144, 64)]:
+        assert wl.er_nnz(a, b, e) == f(a, b, e)
+
+
+def test_init_topology_is_a_uniform_simple_graph(oracle):
+    n_in, n_out, nnz = 300, 200, 5000
+    L = make_layer(oracle, n_in, n_out, nnz)
+    assert L.nnz == nnz and L.rowptr[0] == 0 and L.rowptr[-1] == nnz
+    flat = L.flat()
+    assert np.all(np.diff(flat.astype(np.int64)) > 0)                      # distinct, sorted
+    assert L.colidx.min() >= 0 and L.colidx.max() < n_in
+    assert np.all(L.vel == 0) and np.all(L.bias == 0)
+    # row and column degrees of G(n, M): mean nnz/n, chi-square against the binomial mean
+    rdeg = np.diff(L.rowptr)
+    cdeg = np.bincount(L.colidx, minlength=n_in)
+    for deg, n in ((rdeg, n_out), (cdeg, n_in)):
+        mean = nnz / n
+        chi2 = ((deg - mean) ** 2 / mean).sum()
+        assert abs(chi2 - n) < 6 * np.sqrt(2 * n)
+    # values are the value law evaluated at the flat positions
+    assert np.array_equal(L.val, oracle.weight_values(L.seed, L.layer_id, 0, flat, L.init_limit))
+
+
+# ---------------------------------------------------------------------------- sampler (both modes)
+@pytest.mark.parametrize("n_in,n_out,n_occ,k", [(40, 30, 100, 50),      # sparse mode
+                                                 (12, 10, 60, 30),       # dense mode
+                                                 (8, 4, 20, 12),         # dense mode, fills the matrix
+                                                 (50, 2, 0, 100)])       # init of a fully dense layer
+def test_sampler_invariants(oracle, n_in, n_out, n_occ, k):
+    rng = np.random.default_rng(3)
+    total = n_in * n_out
+    occ = np.sort(rng.choice(total, size=n_occ, replace=False)).astype(np.uint64)
+    got = oracle.sample_positions(n_in, n_out, k, occ, 9, 1, 2)
+    assert got.size == k and np.all(np.diff(got.astype(np.int64)) > 0)
+    assert got.max() < total and np.intersect1d(got, occ).size == 0
+    if n_occ + k == total:
+        assert np.array_equal(np.sort(np.concatenate([got, occ])), np.arange(total, dtype=np.uint64))
+    # sequential definition => nested: the choice for k-1 is contained in the choice for k
+    less = oracle.sample_positions(n_in, n_out, k - 1, occ, 9, 1, 2)
+    dense_mode = total <= 4 * (n_occ + k)
+    if dense_mode == (total <= 4 * (n_occ + k - 1)):
+        assert np.setdiff1d(less, got).size == 0
+    # another generation gives another draw
+    if n_occ + k < total:
+        assert not np.array_equal(got, oracle.sample_positions(n_in, n_out, k, occ, 9, 1, 3))
+
+
+@pytest.mark.parametrize("n_in,n_out,n_occ,k", [(10, 8, 10, 5), (6, 5, 10, 6)])
+def test_sampler_is_uniform_over_empty_positions(oracle, n_in, n_out, n_occ, k):
+    total = n_in * n_out
+    occ = np.arange(0, 2 * n_occ, 2, dtype=np.uint64)
+    counts = np.zeros(total)
+    trials = 4000
+    for g in range(trials):
+        counts[oracle.sample_positions(n_in, n_out, k, occ, 77, 0, g).astype(np.int64)] += 1
+    assert np.all(counts[occ.astype(np.int64)] == 0)
+    empty = np.setdiff1d(np.arange(total), occ.astype(np.int64))
+    expect = trials * k / empty.size
+    chi2 = ((counts[empty] - expect) ** 2 / expect).sum()
+    assert chi2 < empty.size + 6 * np.sqrt(2 * empty.size)
+
+
+# ---------------------------------------------------------------------------- All-ReLU, eq. (3)
+def test_all_relu_definition(oracle):
+    z = np.array([-2.0, 3.0, 0.0, -0.5], dtype=np.float32)
+    even = oracle.all_relu(z, 1, 0, 0.6)
+    odd = oracle.all_relu(z, 1, 1, 0.6)
+    assert np.allclose(even, [1.2, 3.0, 0.0, 0.3], rtol=1e-7)
+    assert np.allclose(odd, [-1.2, 3.0, 0.0, -0.3], rtol=1e-7)
+    x = np.linspace(-3, 3, 601).astype(np.float32)
+    assert np.array_equal(oracle.all_relu(x, 1, 0, 0.0), np.maximum(x, 0))       # alpha = 0: ReLU
+    assert np.array_equal(oracle.all_relu(x, 1, 1, 0.0), np.maximum(x, 0))
+    assert np.array_equal(oracle.all_relu(x, 1, 1, 1.0), x)                      # odd, alpha = 1: identity
+    assert np.array_equal(oracle.all_relu(x, 1, 0, 1.0), np.abs(x))              # even, alpha = 1: |x|
+    assert np.array_equal(oracle.all_relu(x, 0, 0, 0.6), x)                      # output layer: identity
+
+
+# ---------------------------------------------------------------------------- forward / backward, brute force
+def dense_reference(L, x, grad_a):
+    """Dense-with-zeros evaluation in float64 with plain matrix products."""
+    W = L.dense()
+    z = W @ x.astype(np.float64) + L.bias.astype(np.float64)[:, None]
+    if L.act_kind == 0:
+        a, slope = z, np.ones_like(z)
+    else:
+        s = -float(L.alpha) if L.act_parity == 0 else float(L.alpha)
+        a = np.where(z > 0, z, s * z)
+        slope = np.where(z > 0, 1.0, s)
+    dz = grad_a.astype(np.float64) * slope
+    mask = W != 0
+    return z, a, dz, (dz @ x.astype(np.float64).T) * mask, dz.sum(axis=1), W.T @ dz
+
+
+@pytest.mark.parametrize("n_in,n_out,nnz,B,act_kind,parity", [
+    (12, 9, 30, 5, 1, 0), (12, 9, 30, 5, 1, 1), (7, 11, 77, 3, 0, 0),      # last one fully dense
+    (30, 20, 8, 4, 1, 0),                                                   # many empty rows and columns
+    (5, 1, 3, 1, 1, 1), (64, 48, 700, 17, 1, 0)])
+def test_forward_backward_against_dense_matrices(oracle, n_in, n_out, nnz, B, act_kind, parity):
+    L = make_layer(oracle, n_in, n_out, nnz, act_kind, parity, alpha=0.6, seed=21)
+    rng = np.random.default_rng(1)
+    L.bias = rng.standard_normal(n_out).astype(np.float32)
+    x = rng.standard_normal((n_in, B)).astype(np.float32)
+    ga = rng.standard_normal((n_out, B)).astype(np.float32)
+    a = L.forward(x)
+    gx = L.backward(x, ga)
+    z, a_ref, dz, gW, gb, gx_ref = dense_reference(L, x, ga)
+    assert np.allclose(L.z, z, rtol=1e-6, atol=1e-6)
+    assert np.allclose(a, a_ref, rtol=1e-6, atol=1e-6)
+    assert np.allclose(L.dz, dz, rtol=1e-6, atol=1e-6)
+    rows = np.repeat(np.arange(n_out), np.diff(L.rowptr))
+    assert np.allclose(L.grad_val, gW[rows, L.colidx], rtol=1e-5, atol=1e-6)
+    assert np.allclose(L.grad_bias, gb, rtol=1e-5, atol=1e-6)
+    assert np.allclose(gx, gx_ref, rtol=1e-5, atol=1e-6)
+    # independent library routine: scipy CSR times dense
+    S = sp.csr_matrix((L.val.astype(np.float64), L.colidx, L.rowptr), shape=(n_out, n_in))
+    assert np.allclose(L.z, S @ x.astype(np.float64) + L.bias[:, None], rtol=1e-6, atol=1e-6)
+    assert np.allclose(gx, S.T @ L.dz.astype(np.float64), rtol=1e-5, atol=1e-6)
+
+
+def test_softmax_ce_against_scipy(oracle):
+    rng = np.random.default_rng(5)
+    for C, B in [(2, 7), (10, 33)]:
+        z = (rng.standard_normal((C, B)) * 3).astype(np.float32)
+        y = rng.integers(0, C, size=B).astype(np.int32)
+        loss, dz = oracle.softmax_ce(z, y)
+        logp = scipy.special.log_softmax(z.astype(np.float64), axis=0)
+        assert abs(loss - (-logp[y, np.arange(B)].mean())) < 1e-12
+        ref = np.exp(logp)
+        ref[y, np.arange(B)] -= 1
+        assert np.allclose(dz, ref / B, rtol=1e-6, atol=1e-9)
+        assert np.all(np.abs(dz.astype(np.float64).sum(axis=0)) < 1e-7)
+
+
+def test_gradients_against_finite_differences(oracle):
+    """Central differences of the loss of a dense float64 re-evaluation of the network, taken in
+    every stored weight, every bias and every input, against the oracle's backward pass."""
+    dims = (6, 5, 4, 3)
+    rng = np.random.default_rng(8)
+    layers = []
+    for li in range(3):
+        nnz = [14, 11, 12][li]
+        L = make_layer(oracle, dims[li], dims[li + 1], nnz, 0 if li == 2 else 1, (li + 2) % 2, 0.6, seed=31,
+                       layer_id=li, limit=0.9)
+        L.bias = (rng.standard_normal(dims[li + 1]) * 0.3).astype(np.float32)
+        layers.append(L)
+    net = oracle.OracleMLP(layers)
+    B = 4
+    x = rng.standard_normal((dims[0], B)).astype(np.float32)
+    y = rng.integers(0, dims[-1], size=B).astype(np.int32)
+
+    def loss_of(Ws, bs, xin):
+        a = xin
+        for li, (W, b) in enumerate(zip(Ws, bs)):
+            z = W @ a + b[:, None]
+            if li == 2:
+                a = z
+            else:
+                s = -0.6 if (li + 2) % 2 == 0 else 0.6
+                assert np.min(np.abs(z)) > 1e-3          # stay away from the kink
+                a = np.where(z > 0, z, np.float64(np.float32(s)) * z)
+        logp = scipy.special.log_softmax(a, axis=0)
+        return -logp[y, np.arange(B)].mean()
+
+    Ws = [L.dense() for L in layers]
+    bs = [L.bias.astype(np.float64) for L in layers]
+    x64 = x.astype(np.float64)
+    # analytic gradients from the oracle (lr = 0 so that update leaves weights alone)
+    for L in layers:
+        L.lr = np.float32(0.0)
+    net.train_step(x, y)
+    h = 1e-5
+
+    def fd(fun):
+        return (fun(+h) - fun(-h)) / (2 * h)
+
+    for li, L in enumerate(layers):
+        rows = np.repeat(np.arange(L.n_out), np.diff(L.rowptr))
+        for p in range(L.nnz):
+            def f(d, li=li, r=rows[p], c=L.colidx[p]):
+                W2 = [w.copy() for w in Ws]
+                W2[li][r, c] += d
+                return loss_of(W2, bs, x64)
+            assert abs(fd(f) - L.grad_val[p]) <= 1e-5 * max(1.0, abs(L.grad_val[p])) + 2e-7
+        for j in range(L.n_out):
+            def f(d, li=li, j=j):
+                b2 = [b.copy() for b in bs]
+                b2[li][j] += d
+                return loss_of(Ws, b2, x64)
+            assert abs(fd(f) - L.grad_bias[j]) <= 1e-5 * max(1.0, abs(L.grad_bias[j])) + 2e-7
+    # input gradient of the second layer's input = grads[1] (first layer skips its input gradient)
+    a1 = net.acts[1].astype(np.float64)
+    for i in range(dims[1]):
+        for b in range(B):
+            def f(d, i=i, b=b):
+                a = a1.copy()
+                a[i, b] += d
+                z = Ws[1] @ a + bs[1][:, None]
+                a2 = np.where(z > 0, z, np.float64(np.float32(0.6)) * z)
+                z3 = Ws[2] @ a2 + bs[2][:, None]
+                logp = scipy.special.log_softmax(z3, axis=0)
+                return -logp[y, np.arange(B)].mean()
+            assert abs(fd(f) - net.grads[1][i, b]) <= 1e-5 * max(1.0, abs(net.grads[1][i, b])) + 2e-7
+
+
+# ---------------------------------------------------------------------------- momentum SGD, eq. (1)
+def test_momentum_update_matches_two_term_recurrence_and_closed_form(oracle):
+    rng = np.random.default_rng(2)
+    n, steps, lr, mu = 50, 50, 0.01, 0.9
+    L = make_layer(oracle, 10, 5, n, lr=lr, mu=mu)
+    w0 = L.val.astype(np.float64).copy()
+    g_const = rng.standard_normal(n).astype(np.float32)
+    w_prev, w = w0.copy(), w0.copy()
+    for t in range(1, steps + 1):
+        L.grad_val = g_const.copy()
+        L.grad_bias[:] = 0
+        L.update()
+        # eq. (1) literally, in float64, on (w_t, w_{t-1})
+        w_next = w + mu * (w - w_prev) - lr * g_const.astype(np.float64)
+        w_prev, w = w, w_next
+        assert np.allclose(L.val, w, rtol=2e-5, atol=2e-6)
+    # closed form for a constant gradient: w_t = w_0 - lr*g*sum_{s=1..t} (1-mu^s)/(1-mu)
+    coef = sum((1 - mu ** s) / (1 - mu) for s in range(1, steps + 1))
+    assert np.allclose(L.val, w0 - lr * g_const * coef, rtol=2e-5, atol=2e-6)
+    assert np.all(L.bias == 0)
+
+
+# ---------------------------------------------------------------------------- SET evolution, Algorithm 2
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("n_in,n_out,nnz", [(60, 40, 500), (20, 10, 120), (9, 4, 36)])
+def test_evolve_invariants(oracle, mode, n_in, n_out, nnz):
+    zeta = 0.3
+    L = make_layer(oracle, n_in, n_out, nnz, prune_mode=mode, seed=13)
+    rng = np.random.default_rng(4)
+    L.vel = rng.standard_normal(nnz).astype(np.float32)
+    flat0, val0, vel0 = L.flat().copy(), L.val.copy(), L.vel.copy()
+    remove = L.prune_flags(zeta)
+    k = L.evolve(zeta, 1)
+    assert L.nnz == nnz and L.rowptr[-1] == nnz                              # nnz preserved
+    if mode == 0:
+        assert k == int(np.floor(zeta * nnz + 0.5))
+        # removed set = first k of a full sort by (|w| bits, flat position)
+        order = np.lexsort((flat0, val0.view(np.uint32) & 0x7FFFFFFF))
+        assert np.array_equal(np.sort(order[:k]), np.flatnonzero(remove))
+    else:
+        npos, nneg = int((val0 >= 0).sum()), int((val0 < 0).sum())
+        assert k == int(np.floor(zeta * npos + 0.5)) + int(np.floor(zeta * nneg + 0.5))
+        for sel in (val0 >= 0, val0 < 0):
+            idx = np.flatnonzero(sel)
+            kk = int(np.floor(zeta * idx.size + 0.5))
+            order = idx[np.lexsort((flat0[idx], np.abs(val0[idx])))]
+            assert np.array_equal(np.sort(order[:kk]), np.flatnonzero(remove & sel))
+    assert np.abs(val0[remove]).max() <= np.abs(val0[~remove]).min() or mode == 1
+    flat1 = L.flat()
+    assert np.all(np.diff(flat1.astype(np.int64)) > 0)                       # no duplicates, rows sorted
+    # survivors keep weight and velocity bit for bit
+    surv = flat0[~remove]
+    pos_in_new = np.searchsorted(flat1, surv)
+    assert np.array_equal(flat1[pos_in_new], surv)
+    assert np.array_equal(L.val[pos_in_new].view(np.uint32), val0[~remove].view(np.uint32))
+    assert np.array_equal(L.vel[pos_in_new].view(np.uint32), vel0[~remove].view(np.uint32))
+    # new entries: not among the survivors, zero velocity, value from the value law
+    is_new = np.ones(nnz, dtype=bool)
+    is_new[pos_in_new] = False
+    assert is_new.sum() == k and np.all(L.vel[is_new] == 0)
+    assert np.all(np.abs(L.val[is_new]) < L.init_limit) and np.all(L.val[is_new] != 0)
+    assert np.array_equal(L.val[is_new], oracle.weight_values(L.seed, L.layer_id, 1, flat1[is_new], L.init_limit))
+    if nnz == n_in * n_out:                                                  # dense layer: same pattern
+        assert np.array_equal(flat1, flat0)
+
+
+def test_evolve_ties_and_degenerate_cases(oracle):
+    L = make_layer(oracle, 30, 20, 100, seed=3)
+    L.val = np.where(np.arange(100) % 2 == 0, 0.25, -0.25).astype(np.float32)    # all magnitudes equal
+    flat0 = L.flat().copy()
+    remove = L.prune_flags(0.3)
+    assert np.array_equal(np.flatnonzero(remove), np.arange(30))                  # lowest flat positions go
+    # zeta = 0: nothing changes
+    before = (L.rowptr.copy(), L.colidx.copy(), L.val.copy())
+    assert L.evolve(0.0, 1) == 0
+    assert all(np.array_equal(a, b) for a, b in zip(before, (L.rowptr, L.colidx, L.val)))
+    # +0 and -0 compare equal in magnitude; NaN sorts last (never pruned before finite weights)
+    L.val[:] = 1.0
+    L.val[5], L.val[7], L.val[9] = 0.0, -0.0, np.nan
+    remove = L.prune_flags(2.0 / 100)
+    assert set(np.flatnonzero(remove)) == {5, 7}
+    remove = L.prune_flags(0.99)
+    assert not remove[9]
+    # mode 1 (literal Algorithm 2): fractions are taken per sign class
+    L2 = make_layer(oracle, 30, 20, 100, seed=3, prune_mode=1)
+    L2.val = np.concatenate([np.linspace(0.1, 1.0, 10), -np.linspace(0.1, 9.0, 90)]).astype(np.float32)
+    remove = L2.prune_flags(0.3)
+    assert remove[:10].sum() == 3 and remove[10:].sum() == 27
+    assert np.array_equal(np.flatnonzero(remove[:10]), [0, 1, 2])
+    assert np.array_equal(np.flatnonzero(remove[10:]), np.arange(27))
+    assert flat0.size == 100
+
+
+def test_importance_is_row_sum_of_magnitudes(oracle):
+    L = make_layer(oracle, 40, 25, 300, seed=17)
+    assert np.allclose(L.importance(), np.abs(L.dense()).sum(axis=1), rtol=1e-6)
+
+
+# ---------------------------------------------------------------------------- workload generators
+def test_workload_tables_match_the_configurations():
+    w = wl.WORKLOADS
+    assert [l.nnz for l in w["set_mlp_madelon"].layers] == [9000, 5000, 5000, 800]
+    assert [l.nnz for l in w["set_mlp_fmnist"].layers] == [35680, 40000, 40000, 10000]
+    assert [l.nnz for l in w["set_mlp_cifar"].layers] == [141440, 100000, 100000, 40000]
+    assert [l.nnz for l in w["set_mlp_1m"].layers] == [10655360, 20000000, 20000000, 2000000]
+    # All-ReLU alternation: first hidden layer is neuron layer 2 (even), then odd, then even
+    assert [l.act_parity for l in w["set_mlp_fmnist"].layers[:3]] == [0, 1, 0]
+    assert [l.act_kind for l in w["set_mlp_fmnist"].layers] == [1, 1, 1, 0]
+    assert w["set_mlp_fmnist"].steps_per_epoch == 469 and w["set_mlp_cifar"].steps_per_epoch == 391
+    x, y = wl.dataset(w["set_mlp_madelon"], 256)
+    assert x.shape == (256, 500) and x.dtype == np.float32 and set(np.unique(y)) <= {0, 1}
+    blocks = wl.to_batch_blocks(x[:200], 128)
+    assert blocks.shape == (2, 500, 128) and np.array_equal(blocks[1, :, :72], x[128:200].T)
+    assert np.all(blocks[1, :, 72:] == 0)
