@@ -1,0 +1,134 @@
+/*
+ * sparse_set.h -- C ABI of libsparse_set.so: one truly sparse MLP layer trained with Sparse
+ * Evolutionary Training (SET), as in "Truly Sparse Neural Networks at Scale" (arXiv 2102.01732),
+ * computed by hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * A layer maps n_in neurons to n_out neurons.  The paper's problem formulation writes its weights
+ * as W^(l) in R^{n_in x n_out} (w_ij: neuron i of the previous layer -> neuron j); the library
+ * stores the TRANSPOSE Wt in R^{n_out x n_in} as real CSR: row j lists the incoming connections of
+ * neuron j (the set Gamma_j of eq. 4), columns ascending inside a row.  Only stored connections
+ * exist: no dense matrix and no mask is ever formed.
+ *
+ * Dense operands (activations, their gradients) are DEVICE pointers to fp32 in feature-major
+ * layout: element (neuron i, sample b) at i*ld + b, with ld >= B, ld % 4 == 0 and a 16-byte
+ * aligned base pointer.  Columns b >= B of a row are never written and never influence a result.
+ *
+ * Ownership: all device memory belongs to the caller.  `state_dev` holds everything that
+ * persists between calls (CSR, CSC view, weights, velocities, gradients, biases, saved
+ * activation signs); `scratch_dev` holds temporaries of a call and may be shared by all layers
+ * that are used on the same stream.  Both must be 256-byte aligned and at least as large as
+ * sparse_layer_query_sizes reports; the layer keeps both pointers until sparse_layer_destroy.
+ * The sl_layer handle is a small host object owned by the library.
+ *
+ * Streams: `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ * forward / backward / update / sparse_loss_softmax_ce only enqueue work and return.
+ * init / evolve / import / export read counts back and therefore synchronise the stream.
+ * Calls on one layer must be issued from one host thread at a time.
+ *
+ * Errors: every function returns SL_OK (0) or a negative code; nothing is printed and nothing
+ * aborts.  sparse_layer_last_error gives a text for the last failure on that layer.
+ */
+#ifndef SPARSE_SET_H
+#define SPARSE_SET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SL_OK          0
+#define SL_EINVAL     -1   /* null pointer, bad size, B <= 0, B > max_batch, ld < B, misalignment  */
+#define SL_ESTATE     -2   /* call order: backward before forward, update before backward, ...     */
+#define SL_ENOMEM     -3   /* caller's state or scratch buffer too small                           */
+#define SL_EHIP       -4   /* HIP runtime error                                                    */
+#define SL_EOVERFLOW  -5   /* nnz or a dimension exceeds the 32-bit index range                    */
+
+typedef struct sl_layer sl_layer;
+
+#define SL_FLAG_NEED_INPUT_GRAD 1u  /* backward also produces grad_x (false for the first layer)  */
+
+typedef struct sl_config {
+    int64_t  n_in, n_out;
+    double   epsilon;       /* Erdos-Renyi density parameter of the problem formulation:           */
+                            /* nnz = min(floor(epsilon*(n_in+n_out) + 0.5), n_in*n_out)            */
+    int64_t  nnz_override;  /* -1: use epsilon; >= 0: exact number of connections                  */
+    int32_t  act_kind;      /* 0 identity (output layer), 1 All-ReLU (eq. 3)                       */
+    int32_t  act_parity;    /* l % 2 of the receiving neuron layer, input layer being l = 1:       */
+                            /* 0 -> slope -alpha for z <= 0, 1 -> slope +alpha                     */
+    float    alpha;         /* All-ReLU slope                                                      */
+    float    init_limit;    /* new connections ~ U(-init_limit, init_limit), at init and regrowth  */
+    float    lr, momentum;  /* eta and mu of eq. (1)                                               */
+    float    weight_decay;  /* L2 coefficient added to the gradient (0 in every workload)          */
+    uint64_t seed;          /* Philox key = (lo32(seed) ^ layer_id*0x9E3779B9, hi32(seed))         */
+    uint32_t layer_id;
+    int32_t  max_batch;     /* largest B any call will pass                                        */
+    int32_t  prune_mode;    /* 0: remove the round(zeta*nnz) smallest |w|, ties by flat index      */
+                            /* 1: Algorithm 2 literally: fraction zeta of the weights >= 0 and of  */
+                            /*    the weights < 0 separately, each by magnitude                    */
+    uint32_t flags;         /* SL_FLAG_*                                                           */
+} sl_config;
+
+/* Bytes of device memory a layer with this configuration needs.  Host only, no GPU required. */
+int sparse_layer_query_sizes(const sl_config *cfg, size_t *state_bytes, size_t *scratch_bytes);
+
+/* Problem formulation + Algorithm 2 "sparse initialization": builds an Erdos-Renyi topology with
+ * exactly nnz distinct connections (generation 0 of the Philox sampler), draws the weights,
+ * zeroes biases and velocities, builds CSR and (if SL_FLAG_NEED_INPUT_GRAD) the CSC view.
+ * Synchronises the stream. */
+int sparse_layer_init(const sl_config *cfg, void *state_dev, size_t state_bytes, void *scratch_dev,
+                      size_t scratch_bytes, void *hip_stream, sl_layer **out);
+
+/* Forward, eq. (3) applied to z = Wt x + b:  a[j][b] = f_l(bias[j] + sum_{i in Gamma_j} Wt[j,i] x[i][b]).
+ * x_dev [n_in][ldx], a_dev [n_out][lda] (device).  The sign of z needed by backward is kept in
+ * the layer's state.  Asynchronous. */
+int sparse_layer_forward(sl_layer *layer, const float *x_dev, int64_t ldx, int32_t B, float *a_dev,
+                         int64_t lda, void *hip_stream);
+
+/* Backward of the same minibatch (must follow forward with the same B):
+ *   dz = grad_a * f_l'(z)                     (f' at z = 0 is the "z <= 0" branch of eq. 3)
+ *   grad_bias[j] = sum_b dz[j][b]
+ *   grad_val[p]  = sum_b dz[j][b] * x[i][b]   for every stored connection p = (j,i) only
+ *   grad_x[i][b] = sum_{j:(j,i) stored} Wt[j,i] * dz[j][b]   (weights before the update)
+ * grad_a_dev [n_out][ldg]; x_dev is the x passed to forward; grad_x_dev [n_in][ldgx] must be
+ * non-NULL iff the layer was created with SL_FLAG_NEED_INPUT_GRAD.  The 1/B of the minibatch
+ * mean (Algorithm 1's worker gradient) is carried by grad_a of the output layer.  Asynchronous. */
+int sparse_layer_backward(sl_layer *layer, const float *x_dev, int64_t ldx, const float *grad_a_dev,
+                          int64_t ldg, int32_t B, float *grad_x_dev, int64_t ldgx, void *hip_stream);
+
+/* Momentum SGD over the stored connections and the biases, eq. (1) in velocity form:
+ * vel <- mu*vel - eta*(grad + weight_decay*w);  w <- w + vel.  Must follow backward.  Asynchronous. */
+int sparse_layer_update(sl_layer *layer, void *hip_stream);
+
+/* Algorithm 2's weight pruning-regrowing cycle: removes k connections (see prune_mode), draws k
+ * distinct empty positions with the Philox sampler at `generation` (>= 1, < 2^32; a different
+ * value per call), gives them fresh weights and zero velocity, and rebuilds CSR and the CSC
+ * view.  nnz is unchanged.  k = floor(zeta*nnz + 0.5) in double.  Synchronises the stream. */
+int sparse_layer_evolve(sl_layer *layer, double zeta, uint64_t generation, void *hip_stream);
+
+int sparse_layer_destroy(sl_layer *layer);
+
+/* Softmax + cross-entropy over C output neurons (the loss is unnamed in the paper).
+ * z_dev [C][ldz], y_dev int32[B] (device) -> dz_dev [C][lddz] = (softmax(z) - onehot(y)) / B and
+ * *loss_sum_dev += sum_b -log softmax(z)[y_b] (device float; the caller zeroes and averages it;
+ * may be NULL).  C <= 1024.  Asynchronous. */
+int sparse_loss_softmax_ce(const float *z_dev, int64_t ldz, const int32_t *y_dev, int32_t B, int32_t C,
+                           float *dz_dev, int64_t lddz, float *loss_sum_dev, void *hip_stream);
+
+/* Inspection / parity / checkpoint.  Host pointers; each call synchronises the layer's last
+ * stream.  Any output pointer may be NULL.  Arrays are in CSR order. */
+int sparse_layer_nnz(const sl_layer *layer, int64_t *nnz);
+int sparse_layer_export_csr(sl_layer *layer, int32_t *rowptr, int32_t *colidx, float *val, float *vel,
+                            float *bias, float *bias_vel);
+/* Replaces pattern and values; nnz must equal the layer's nnz, rows must be sorted and distinct. */
+int sparse_layer_import_csr(sl_layer *layer, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                            const float *vel, const float *bias, const float *bias_vel);
+int sparse_layer_export_grad(sl_layer *layer, float *grad_val, float *grad_bias);
+int sparse_layer_set_lr(sl_layer *layer, float lr);
+const char *sparse_layer_last_error(const sl_layer *layer);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSE_SET_H */

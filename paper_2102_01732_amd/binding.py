@@ -1,0 +1,239 @@
+"""ctypes binding of libsparse_set.so: argument marshalling only.
+
+Every step of the training path runs in the library's HIP kernels; torch is used for device
+buffers and for the current stream handle.  There is no CPU fallback: ``lib()`` raises if the
+shared library has not been built (``python -m paper_2102_01732_amd.build``).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsparse_set.so")
+_lib = None
+
+SL_OK, SL_EINVAL, SL_ESTATE, SL_ENOMEM, SL_EHIP, SL_EOVERFLOW = 0, -1, -2, -3, -4, -5
+SL_FLAG_NEED_INPUT_GRAD = 1
+
+EXPORTS = [
+    "sparse_layer_query_sizes", "sparse_layer_init", "sparse_layer_forward", "sparse_layer_backward",
+    "sparse_layer_update", "sparse_layer_evolve", "sparse_layer_destroy", "sparse_loss_softmax_ce",
+    "sparse_layer_nnz", "sparse_layer_export_csr", "sparse_layer_import_csr", "sparse_layer_export_grad",
+    "sparse_layer_set_lr", "sparse_layer_last_error",
+]
+
+
+class SlConfig(C.Structure):
+    _fields_ = [
+        ("n_in", C.c_int64), ("n_out", C.c_int64), ("epsilon", C.c_double), ("nnz_override", C.c_int64),
+        ("act_kind", C.c_int32), ("act_parity", C.c_int32), ("alpha", C.c_float), ("init_limit", C.c_float),
+        ("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float), ("seed", C.c_uint64),
+        ("layer_id", C.c_uint32), ("max_batch", C.c_int32), ("prune_mode", C.c_int32), ("flags", C.c_uint32),
+    ]
+
+
+class SparseSetError(RuntimeError):
+    def __init__(self, code: int, where: str, text: str = ""):
+        super().__init__(f"{where} failed with code {code}" + (f": {text}" if text else ""))
+        self.code = code
+
+
+def lib():
+    """Loads libsparse_set.so; raises if it is missing (there is no other implementation)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2102_01732_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i64, i32, f32p, i32p = C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p
+        L.sparse_layer_query_sizes.argtypes = [C.POINTER(SlConfig), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.sparse_layer_init.argtypes = [C.POINTER(SlConfig), vp, C.c_size_t, vp, C.c_size_t, vp, C.POINTER(vp)]
+        L.sparse_layer_forward.argtypes = [vp, f32p, i64, i32, f32p, i64, vp]
+        L.sparse_layer_backward.argtypes = [vp, f32p, i64, f32p, i64, i32, f32p, i64, vp]
+        L.sparse_layer_update.argtypes = [vp, vp]
+        L.sparse_layer_evolve.argtypes = [vp, C.c_double, C.c_uint64, vp]
+        L.sparse_layer_destroy.argtypes = [vp]
+        L.sparse_loss_softmax_ce.argtypes = [f32p, i64, i32p, i32, i32, f32p, i64, f32p, vp]
+        L.sparse_layer_nnz.argtypes = [vp, C.POINTER(i64)]
+        L.sparse_layer_export_csr.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.sparse_layer_import_csr.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.sparse_layer_export_grad.argtypes = [vp, vp, vp]
+        L.sparse_layer_set_lr.argtypes = [vp, C.c_float]
+        L.sparse_layer_last_error.argtypes = [vp]
+        L.sparse_layer_last_error.restype = C.c_char_p
+        for name in EXPORTS:
+            if name != "sparse_layer_last_error":
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def make_config(n_in, n_out, *, epsilon=0.0, nnz=-1, act_kind=1, act_parity=0, alpha=0.6, init_limit=0.1, lr=0.01,
+                momentum=0.9, weight_decay=0.0, seed=0, layer_id=0, max_batch=128, prune_mode=0,
+                need_input_grad=True) -> SlConfig:
+    return SlConfig(n_in, n_out, float(epsilon), int(nnz), act_kind, act_parity, float(alpha), float(init_limit),
+                    float(lr), float(momentum), float(weight_decay), int(seed), int(layer_id), int(max_batch),
+                    int(prune_mode), SL_FLAG_NEED_INPUT_GRAD if need_input_grad else 0)
+
+
+def query_sizes(cfg: SlConfig):
+    sb, cb = C.c_size_t(0), C.c_size_t(0)
+    rc = lib().sparse_layer_query_sizes(C.byref(cfg), C.byref(sb), C.byref(cb))
+    if rc != SL_OK:
+        raise SparseSetError(rc, "sparse_layer_query_sizes")
+    return sb.value, cb.value
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+class SparseLayer:
+    """One sparse layer living in caller-owned torch buffers."""
+
+    def __init__(self, cfg: SlConfig, device="cuda:0", scratch: Optional[torch.Tensor] = None):
+        self.cfg = cfg
+        self.device = torch.device(device)
+        sb, cb = query_sizes(cfg)
+        self.state = torch.empty(sb + 256, dtype=torch.uint8, device=self.device)
+        if scratch is None or scratch.numel() < cb:
+            scratch = torch.empty(cb + 256, dtype=torch.uint8, device=self.device)
+        self.scratch = scratch
+        assert self.state.data_ptr() % 256 == 0 and self.scratch.data_ptr() % 256 == 0
+        self.handle = C.c_void_p(None)
+        rc = lib().sparse_layer_init(C.byref(cfg), self.state.data_ptr(), self.state.numel(), self.scratch.data_ptr(),
+                                     self.scratch.numel(), _stream(), C.byref(self.handle))
+        if rc != SL_OK:
+            raise SparseSetError(rc, "sparse_layer_init")
+        n = C.c_int64(0)
+        lib().sparse_layer_nnz(self.handle, C.byref(n))
+        self.nnz = n.value
+        self.n_in, self.n_out = cfg.n_in, cfg.n_out
+
+    def _check(self, rc: int, where: str):
+        if rc != SL_OK:
+            raise SparseSetError(rc, where, lib().sparse_layer_last_error(self.handle).decode())
+
+    def forward(self, x: torch.Tensor, B: int, a: torch.Tensor):
+        self._check(lib().sparse_layer_forward(self.handle, x.data_ptr(), x.stride(0), B, a.data_ptr(), a.stride(0),
+                                               _stream()), "sparse_layer_forward")
+
+    def backward(self, x: torch.Tensor, grad_a: torch.Tensor, B: int, grad_x: Optional[torch.Tensor]):
+        self._check(lib().sparse_layer_backward(self.handle, x.data_ptr(), x.stride(0), grad_a.data_ptr(),
+                                                grad_a.stride(0), B, _ptr(grad_x),
+                                                grad_x.stride(0) if grad_x is not None else 0, _stream()),
+                    "sparse_layer_backward")
+
+    def update(self):
+        self._check(lib().sparse_layer_update(self.handle, _stream()), "sparse_layer_update")
+
+    def evolve(self, zeta: float, generation: int):
+        self._check(lib().sparse_layer_evolve(self.handle, float(zeta), int(generation), _stream()),
+                    "sparse_layer_evolve")
+
+    def set_lr(self, lr: float):
+        self._check(lib().sparse_layer_set_lr(self.handle, float(lr)), "sparse_layer_set_lr")
+
+    def export_csr(self):
+        rowptr = np.zeros(self.n_out + 1, np.int32)
+        colidx = np.zeros(max(self.nnz, 1), np.int32)
+        val = np.zeros(max(self.nnz, 1), np.float32)
+        vel = np.zeros(max(self.nnz, 1), np.float32)
+        bias = np.zeros(self.n_out, np.float32)
+        bias_vel = np.zeros(self.n_out, np.float32)
+        self._check(lib().sparse_layer_export_csr(self.handle, rowptr.ctypes.data, colidx.ctypes.data, val.ctypes.data,
+                                                  vel.ctypes.data, bias.ctypes.data, bias_vel.ctypes.data),
+                    "sparse_layer_export_csr")
+        n = self.nnz
+        return rowptr, colidx[:n], val[:n], vel[:n], bias, bias_vel
+
+    def import_csr(self, rowptr, colidx, val, vel=None, bias=None, bias_vel=None):
+        arrs = [np.ascontiguousarray(rowptr, np.int32), np.ascontiguousarray(colidx, np.int32),
+                np.ascontiguousarray(val, np.float32)]
+        opt = [None if a is None else np.ascontiguousarray(a, np.float32) for a in (vel, bias, bias_vel)]
+        self._check(lib().sparse_layer_import_csr(self.handle, *[a.ctypes.data for a in arrs],
+                                                  *[None if a is None else a.ctypes.data for a in opt]),
+                    "sparse_layer_import_csr")
+
+    def export_grad(self):
+        g = np.zeros(max(self.nnz, 1), np.float32)
+        gb = np.zeros(self.n_out, np.float32)
+        self._check(lib().sparse_layer_export_grad(self.handle, g.ctypes.data, gb.ctypes.data),
+                    "sparse_layer_export_grad")
+        return g[: self.nnz], gb
+
+    def close(self):
+        if self.handle:
+            lib().sparse_layer_destroy(self.handle)
+            self.handle = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def softmax_ce(z: torch.Tensor, y: torch.Tensor, B: int, n_classes: int, dz: torch.Tensor,
+               loss_sum: Optional[torch.Tensor] = None):
+    rc = lib().sparse_loss_softmax_ce(z.data_ptr(), z.stride(0), y.data_ptr(), B, n_classes, dz.data_ptr(),
+                                      dz.stride(0), _ptr(loss_sum), _stream())
+    if rc != SL_OK:
+        raise SparseSetError(rc, "sparse_loss_softmax_ce")
+
+
+class SparseMLP:
+    """Chain of sparse layers + softmax cross-entropy: the training loop of Algorithm 2 (train for
+    an epoch of minibatches, then prune and regrow every sparse layer).  Only calls into the
+    library; activations and gradients are preallocated feature-major buffers [n][ld]."""
+
+    def __init__(self, layer_specs: Sequence, *, alpha: float, lr: float, momentum: float, seed: int, max_batch: int,
+                 prune_mode: int = 0, weight_decay: float = 0.0, device="cuda:0"):
+        self.device = torch.device(device)
+        self.max_batch = max_batch
+        self.ld = (max_batch + 31) // 32 * 32
+        cfgs = [make_config(s.n_in, s.n_out, nnz=s.nnz, act_kind=s.act_kind, act_parity=s.act_parity, alpha=alpha,
+                            init_limit=s.init_limit, lr=lr, momentum=momentum, weight_decay=weight_decay, seed=seed,
+                            layer_id=s.layer_id, max_batch=max_batch, prune_mode=prune_mode,
+                            need_input_grad=(li > 0)) for li, s in enumerate(layer_specs)]
+        scratch_bytes = max(query_sizes(c)[1] for c in cfgs)
+        self.scratch = torch.empty(scratch_bytes + 256, dtype=torch.uint8, device=self.device)
+        self.layers: List[SparseLayer] = [SparseLayer(c, device, self.scratch) for c in cfgs]
+        self.acts = [torch.zeros((s.n_out, self.ld), dtype=torch.float32, device=self.device) for s in layer_specs]
+        self.grads = [torch.zeros((s.n_out, self.ld), dtype=torch.float32, device=self.device) for s in layer_specs]
+        self.loss_sum = torch.zeros(1, dtype=torch.float32, device=self.device)
+        self.n_classes = layer_specs[-1].n_out
+
+    def forward(self, x: torch.Tensor, B: int) -> torch.Tensor:
+        cur = x
+        for layer, a in zip(self.layers, self.acts):
+            layer.forward(cur, B, a)
+            cur = a
+        return cur
+
+    def train_step(self, x: torch.Tensor, y: torch.Tensor, B: int):
+        """x [n_in][ld>=B] feature-major, y int32 [B]."""
+        zL = self.forward(x, B)
+        softmax_ce(zL, y, B, self.n_classes, self.grads[-1], self.loss_sum)
+        for li in range(len(self.layers) - 1, -1, -1):
+            xin = x if li == 0 else self.acts[li - 1]
+            self.layers[li].backward(xin, self.grads[li], B, self.grads[li - 1] if li > 0 else None)
+        for layer in self.layers:
+            layer.update()
+
+    def evolve(self, zeta: float, generation: int):
+        for layer in self.layers:
+            layer.evolve(zeta, generation)
+
+    def close(self):
+        for layer in self.layers:
+            layer.close()

@@ -1,0 +1,424 @@
+// C ABI of libsparse_set.so (see include/sparse_set.h): argument checking, carving of the caller's
+// state and scratch buffers, call-order tracking.  No kernel lives here.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "sl_internal.h"
+
+namespace sl {
+
+int set_err(sl_layer *L, int code, const char *fmt, ...)
+{
+    if (L) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(L->err, sizeof(L->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+static size_t take(size_t &cursor, size_t bytes)
+{
+    const size_t at = cursor;
+    cursor = align_up(cursor + bytes);
+    return at;
+}
+
+int64_t config_nnz(const sl_config &c)
+{
+    const double total = (double)c.n_in * (double)c.n_out;
+    double want = c.nnz_override >= 0 ? (double)c.nnz_override : floor(c.epsilon * (double)(c.n_in + c.n_out) + 0.5);
+    if (want > total) want = total;
+    if (want < 0) want = 0;
+    return (int64_t)want;
+}
+
+// Rows longer than the returned length are cut into virtual rows.  Wide matrices keep their rows
+// whole unless one is far above the mean; matrices with few rows (narrow output layers) are cut so
+// that about 8192 groups exist.
+int choose_seg(int64_t n_rows, int64_t nnz)
+{
+    int64_t seg;
+    if (n_rows >= 8192) seg = 4 * ((nnz + n_rows - 1) / (n_rows > 0 ? n_rows : 1));
+    else seg = (nnz + 8191) / 8192;
+    if (seg < 64) seg = 64;
+    if (seg > (1 << 30)) seg = 1 << 30;
+    return (int)seg;
+}
+
+// Window of candidates that yields k accepted positions with overwhelming probability: the
+// expected number of draws is M*ln((M-occ)/(M-occ-k)); 5 % and eight standard deviations are
+// added on top.
+int64_t sampler_window(double M, double n_occ, double k)
+{
+    if (k <= 0) return 0;
+    const double rest = M - n_occ - k;
+    const double expect = rest > 0 ? M * log1p(k / rest) : 64.0 * M;
+    return (int64_t)ceil(1.05 * expect + 8.0 * sqrt(expect) + 1024.0);
+}
+
+static int round_up32(int x) { return (x + 31) & ~31; }
+
+int plan_state(const sl_config &c, int64_t nnz, StatePlan *sp)
+{
+    size_t cur = 0;
+    const size_t n = (size_t)nnz, ni = (size_t)c.n_in, no = (size_t)c.n_out;
+    const size_t ldz = (size_t)round_up32(c.max_batch);
+    const bool csc = (c.flags & SL_FLAG_NEED_INPUT_GRAD) != 0;
+    sp->rowptr = take(cur, 4 * (no + 1));
+    sp->colidx = take(cur, 4 * n);
+    sp->val = take(cur, 4 * n);
+    sp->vel = take(cur, 4 * n);
+    sp->grad = take(cur, 4 * n);
+    sp->bias = take(cur, 4 * no);
+    sp->bias_vel = take(cur, 4 * no);
+    sp->grad_bias = take(cur, 4 * no);
+    if (csc) {
+        sp->colptr = take(cur, 4 * (ni + 1));
+        sp->rowidx = take(cur, 4 * n);
+        sp->csr_pos = take(cur, 4 * n);
+        sp->valT = take(cur, 4 * n);
+        sp->velT = take(cur, 4 * n);
+    }
+    sp->mask = take(cur, no * (ldz / 4));
+    sp->dz = take(cur, 4 * no * ldz);
+    sp->nv_cap_f = (int)(no + n / 64 + 2);
+    sp->f_vptr = take(cur, 4 * ((size_t)sp->nv_cap_f + 1));
+    sp->f_v2row = take(cur, 4 * (size_t)sp->nv_cap_f);
+    sp->f_rvptr = take(cur, 4 * (no + 1));
+    if (csc) {
+        sp->nv_cap_b = (int)(ni + n / 64 + 2);
+        sp->b_vptr = take(cur, 4 * ((size_t)sp->nv_cap_b + 1));
+        sp->b_v2row = take(cur, 4 * (size_t)sp->nv_cap_b);
+        sp->b_rvptr = take(cur, 4 * (ni + 1));
+    }
+    sp->sel = take(cur, 2 * sizeof(SelState));
+    sp->total = cur;
+    return SL_OK;
+}
+
+int plan_scratch(const sl_config &c, int64_t nnz, ScratchPlan *cp)
+{
+    const size_t n = (size_t)nnz, ni = (size_t)c.n_in, no = (size_t)c.n_out;
+    const size_t ldz = (size_t)round_up32(c.max_batch);
+    const bool csc = (c.flags & SL_FLAG_NEED_INPUT_GRAD) != 0;
+    const double M = (double)c.n_in * (double)c.n_out;
+    cp->dense_mode = M <= 4.0 * (double)nnz;
+    if (cp->dense_mode) cp->w_cap = (int64_t)M;
+    else cp->w_cap = 2 * sampler_window(M, 0.0, (double)nnz);
+    if (cp->w_cap < (int64_t)n) cp->w_cap = (int64_t)n;
+    const size_t w = (size_t)cp->w_cap;
+    // the regions of the training passes and of init/evolve never live at the same time
+    size_t cur = 0;
+    const size_t nv_cap = (no > (csc ? ni : 0) ? no : ni) + n / 64 + 2;
+    cp->partial = take(cur, 4 * nv_cap * ldz);
+    const size_t train_end = cur;
+    cur = 0;
+    cp->tie64 = take(cur, 8 * (n + 1));
+    cp->trank = take(cur, 8 * (n + 1));
+    cp->keep = take(cur, 4 * (n + 1));
+    cp->kscan = take(cur, 4 * (n + 1));
+    cp->s_col = take(cur, 4 * n);
+    cp->s_val = take(cur, 4 * n);
+    cp->s_vel = take(cur, 4 * n);
+    cp->rowptr_s = take(cur, 4 * (no + 1));
+    cp->new_p = take(cur, 8 * n);
+    cp->keyA = take(cur, 8 * w);
+    cp->keyB = take(cur, 8 * w);
+    cp->payA = take(cur, 4 * w);
+    cp->payB = take(cur, 4 * w);
+    const size_t fl = (w > (ni > no ? ni : no) ? w : (ni > no ? ni : no)) + 1;
+    cp->f0 = take(cur, 4 * fl);
+    cp->f1 = take(cur, 4 * fl);
+    cp->f2 = take(cur, 4 * fl);
+    cp->f3 = take(cur, 4 * fl);
+    cp->temp_bytes = ((size_t)32 << 20) + 2 * (w > n ? w : n);
+    cp->temp = take(cur, cp->temp_bytes);
+    cp->small = take(cur, 1024);
+    cp->total = cur > train_end ? cur : train_end;
+    return SL_OK;
+}
+
+static int check_config(const sl_config *c, int64_t *nnz_out)
+{
+    if (!c) return SL_EINVAL;
+    if (c->n_in <= 0 || c->n_out <= 0 || c->max_batch <= 0) return SL_EINVAL;
+    if (c->nnz_override < -1 || (c->nnz_override < 0 && !(c->epsilon >= 0.0))) return SL_EINVAL;
+    if (c->act_kind < 0 || c->act_kind > 1 || c->act_parity < 0 || c->act_parity > 1) return SL_EINVAL;
+    if (c->prune_mode < 0 || c->prune_mode > 1) return SL_EINVAL;
+    if (!(c->init_limit > 0.f)) return SL_EINVAL;
+    if (c->n_in >= ((int64_t)1 << 31) - 1 || c->n_out >= ((int64_t)1 << 31) - 1) return SL_EOVERFLOW;
+    if (c->max_batch > (1 << 20)) return SL_EOVERFLOW;
+    const int64_t nnz = config_nnz(*c);
+    // 32-bit offsets and 32-bit sampler payloads
+    if (nnz >= ((int64_t)1 << 30)) return SL_EOVERFLOW;
+    const double M = (double)c->n_in * (double)c->n_out;
+    if (M <= 4.0 * (double)nnz && M >= 2147483647.0) return SL_EOVERFLOW;
+    if (M > 4.0 * (double)nnz && 2 * sampler_window(M, 0.0, (double)nnz) >= ((int64_t)1 << 32) - 2) return SL_EOVERFLOW;
+    *nnz_out = nnz;
+    return SL_OK;
+}
+
+}  // namespace sl
+
+using namespace sl;
+
+extern "C" {
+
+int sparse_layer_query_sizes(const sl_config *cfg, size_t *state_bytes, size_t *scratch_bytes)
+{
+    int64_t nnz = 0;
+    int rc = check_config(cfg, &nnz);
+    if (rc) return rc;
+    StatePlan sp;
+    ScratchPlan cp;
+    plan_state(*cfg, nnz, &sp);
+    plan_scratch(*cfg, nnz, &cp);
+    if (state_bytes) *state_bytes = sp.total;
+    if (scratch_bytes) *scratch_bytes = cp.total;
+    return SL_OK;
+}
+
+int sparse_layer_init(const sl_config *cfg, void *state_dev, size_t state_bytes, void *scratch_dev,
+                      size_t scratch_bytes, void *hip_stream, sl_layer **out)
+{
+    if (!out) return SL_EINVAL;
+    *out = nullptr;
+    int64_t nnz = 0;
+    int rc = check_config(cfg, &nnz);
+    if (rc) return rc;
+    if (!state_dev || !scratch_dev) return SL_EINVAL;
+    if (((uintptr_t)state_dev & 255) || ((uintptr_t)scratch_dev & 255)) return SL_EINVAL;
+    sl_layer *L = new (std::nothrow) sl_layer();
+    if (!L) return SL_ENOMEM;
+    L->cfg = *cfg;
+    L->nnz = nnz;
+    plan_state(*cfg, nnz, &L->sp);
+    plan_scratch(*cfg, nnz, &L->cp);
+    if (state_bytes < L->sp.total || scratch_bytes < L->cp.total) {
+        delete L;
+        return SL_ENOMEM;
+    }
+    L->ldz = round_up32(cfg->max_batch);
+    L->ldm = L->ldz / 4;
+    L->has_csc = (cfg->flags & SL_FLAG_NEED_INPUT_GRAD) != 0;
+    L->state = (char *)state_dev; L->state_bytes = state_bytes;
+    L->scratch = (char *)scratch_dev; L->scratch_bytes = scratch_bytes;
+    char *b = L->state;
+    const StatePlan &sp = L->sp;
+    L->rowptr = (int *)(b + sp.rowptr); L->colidx = (int *)(b + sp.colidx);
+    L->val = (float *)(b + sp.val); L->vel = (float *)(b + sp.vel); L->grad = (float *)(b + sp.grad);
+    L->bias = (float *)(b + sp.bias); L->bias_vel = (float *)(b + sp.bias_vel); L->grad_bias = (float *)(b + sp.grad_bias);
+    if (L->has_csc) {
+        L->colptr = (int *)(b + sp.colptr); L->rowidx = (int *)(b + sp.rowidx); L->csr_pos = (int *)(b + sp.csr_pos);
+        L->valT = (float *)(b + sp.valT); L->velT = (float *)(b + sp.velT);
+        L->bwd.vptr_store = (int *)(b + sp.b_vptr); L->bwd.v2row_store = (int *)(b + sp.b_v2row);
+        L->bwd.rvptr_store = (int *)(b + sp.b_rvptr); L->bwd.nv_cap = sp.nv_cap_b;
+    }
+    L->mask = (uint8_t *)(b + sp.mask); L->dz = (float *)(b + sp.dz);
+    L->fwd.vptr_store = (int *)(b + sp.f_vptr); L->fwd.v2row_store = (int *)(b + sp.f_v2row);
+    L->fwd.rvptr_store = (int *)(b + sp.f_rvptr); L->fwd.nv_cap = sp.nv_cap_f;
+    L->sel = (SelState *)(b + sp.sel);
+    hipStream_t s = (hipStream_t)hip_stream;
+    L->last_stream = s;
+    rc = topo_init(L, s);
+    if (rc == SL_OK) {
+        hipError_t e = hipStreamSynchronize(s);
+        if (e != hipSuccess) rc = SL_EHIP;
+    }
+    if (rc) {
+        delete L;
+        return rc;
+    }
+    *out = L;
+    return SL_OK;
+}
+
+static int check_dense(sl_layer *L, const void *p, int64_t ld, int B, const char *what)
+{
+    if (!p) return set_err(L, SL_EINVAL, "%s is null", what);
+    if (ld < B || (ld & 3)) return set_err(L, SL_EINVAL, "%s: leading dimension %lld must be >= B and a multiple of 4", what, (long long)ld);
+    if ((uintptr_t)p & 15) return set_err(L, SL_EINVAL, "%s must be 16-byte aligned", what);
+    return SL_OK;
+}
+
+int sparse_layer_forward(sl_layer *L, const float *x_dev, int64_t ldx, int32_t B, float *a_dev, int64_t lda,
+                         void *hip_stream)
+{
+    if (!L) return SL_EINVAL;
+    if (B <= 0 || B > L->cfg.max_batch) return set_err(L, SL_EINVAL, "B = %d outside 1..max_batch = %d", B, L->cfg.max_batch);
+    int rc = check_dense(L, x_dev, ldx, B, "x");
+    if (rc) return rc;
+    rc = check_dense(L, a_dev, lda, B, "a");
+    if (rc) return rc;
+    L->last_stream = (hipStream_t)hip_stream;
+    rc = launch_forward(L, x_dev, ldx, B, a_dev, lda, L->last_stream);
+    if (rc) return rc;
+    L->phase = 1;
+    L->last_B = B;
+    return SL_OK;
+}
+
+int sparse_layer_backward(sl_layer *L, const float *x_dev, int64_t ldx, const float *grad_a_dev, int64_t ldg,
+                          int32_t B, float *grad_x_dev, int64_t ldgx, void *hip_stream)
+{
+    if (!L) return SL_EINVAL;
+    if (L->phase < 1) return set_err(L, SL_ESTATE, "backward called before forward");
+    if (B != L->last_B) return set_err(L, SL_ESTATE, "backward with B = %d after forward with B = %d", B, L->last_B);
+    int rc = check_dense(L, x_dev, ldx, B, "x");
+    if (rc) return rc;
+    rc = check_dense(L, grad_a_dev, ldg, B, "grad_a");
+    if (rc) return rc;
+    if (L->has_csc) {
+        rc = check_dense(L, grad_x_dev, ldgx, B, "grad_x");
+        if (rc) return rc;
+    } else if (grad_x_dev) {
+        return set_err(L, SL_EINVAL, "grad_x given but the layer was created without SL_FLAG_NEED_INPUT_GRAD");
+    }
+    L->last_stream = (hipStream_t)hip_stream;
+    rc = launch_backward(L, x_dev, ldx, grad_a_dev, ldg, B, grad_x_dev, ldgx, L->last_stream);
+    if (rc) return rc;
+    L->phase = 2;
+    return SL_OK;
+}
+
+int sparse_layer_update(sl_layer *L, void *hip_stream)
+{
+    if (!L) return SL_EINVAL;
+    if (L->phase < 2) return set_err(L, SL_ESTATE, "update called before backward");
+    L->last_stream = (hipStream_t)hip_stream;
+    int rc = launch_update(L, L->last_stream);
+    if (rc) return rc;
+    L->phase = 0;
+    return SL_OK;
+}
+
+int sparse_layer_evolve(sl_layer *L, double zeta, uint64_t generation, void *hip_stream)
+{
+    if (!L) return SL_EINVAL;
+    if (!(zeta >= 0.0 && zeta <= 1.0)) return set_err(L, SL_EINVAL, "zeta = %g outside [0,1]", zeta);
+    if (generation == 0 || generation >= ((uint64_t)1 << 32)) return set_err(L, SL_EINVAL, "generation must be in 1..2^32-1");
+    L->last_stream = (hipStream_t)hip_stream;
+    int rc = topo_evolve(L, zeta, (uint32_t)generation, L->last_stream);
+    if (rc) return rc;
+    hipError_t e = hipStreamSynchronize(L->last_stream);
+    if (e != hipSuccess) return set_err(L, SL_EHIP, "evolve: %s", hipGetErrorString(e));
+    L->phase = 0;
+    return SL_OK;
+}
+
+int sparse_layer_destroy(sl_layer *L)
+{
+    if (!L) return SL_EINVAL;
+    delete L;
+    return SL_OK;
+}
+
+int sparse_loss_softmax_ce(const float *z_dev, int64_t ldz, const int32_t *y_dev, int32_t B, int32_t C, float *dz_dev,
+                           int64_t lddz, float *loss_sum_dev, void *hip_stream)
+{
+    if (!z_dev || !y_dev || !dz_dev || B <= 0 || C <= 0 || C > 1024 || ldz < B || lddz < B) return SL_EINVAL;
+    return launch_softmax_ce(z_dev, ldz, y_dev, B, C, dz_dev, lddz, loss_sum_dev, (hipStream_t)hip_stream);
+}
+
+int sparse_layer_nnz(const sl_layer *L, int64_t *nnz)
+{
+    if (!L || !nnz) return SL_EINVAL;
+    *nnz = L->nnz;
+    return SL_OK;
+}
+
+static int copy_out(sl_layer *L, void *host, const void *dev, size_t bytes)
+{
+    if (!host || bytes == 0) return SL_OK;
+    SL_HIP(L, hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, L->last_stream));
+    return SL_OK;
+}
+
+int sparse_layer_export_csr(sl_layer *L, int32_t *rowptr, int32_t *colidx, float *val, float *vel, float *bias,
+                            float *bias_vel)
+{
+    if (!L) return SL_EINVAL;
+    int rc = SL_OK;
+    if (vel) rc = topo_sync_csr_vel(L, L->last_stream);
+    const size_t n = (size_t)L->nnz, no = (size_t)L->cfg.n_out;
+    if (!rc) rc = copy_out(L, rowptr, L->rowptr, 4 * (no + 1));
+    if (!rc) rc = copy_out(L, colidx, L->colidx, 4 * n);
+    if (!rc) rc = copy_out(L, val, L->val, 4 * n);
+    if (!rc) rc = copy_out(L, vel, L->vel, 4 * n);
+    if (!rc) rc = copy_out(L, bias, L->bias, 4 * no);
+    if (!rc) rc = copy_out(L, bias_vel, L->bias_vel, 4 * no);
+    if (rc) return rc;
+    SL_HIP(L, hipStreamSynchronize(L->last_stream));
+    return SL_OK;
+}
+
+int sparse_layer_import_csr(sl_layer *L, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                            const float *vel, const float *bias, const float *bias_vel)
+{
+    if (!L || !rowptr || !colidx || !val) return SL_EINVAL;
+    const int64_t n = L->nnz, no = L->cfg.n_out, ni = L->cfg.n_in;
+    if (rowptr[0] != 0 || rowptr[no] != n) return set_err(L, SL_EINVAL, "import: rowptr does not describe %lld entries", (long long)n);
+    for (int64_t r = 0; r < no; ++r) {
+        if (rowptr[r + 1] < rowptr[r]) return set_err(L, SL_EINVAL, "import: rowptr decreases at row %lld", (long long)r);
+        for (int32_t p = rowptr[r]; p < rowptr[r + 1]; ++p) {
+            if (colidx[p] < 0 || colidx[p] >= ni) return set_err(L, SL_EINVAL, "import: column out of range at %d", p);
+            if (p > rowptr[r] && colidx[p] <= colidx[p - 1]) return set_err(L, SL_EINVAL, "import: row %lld not strictly ascending", (long long)r);
+        }
+    }
+    hipStream_t s = L->last_stream;
+    SL_HIP(L, hipStreamSynchronize(s));
+    SL_HIP(L, hipMemcpy(L->rowptr, rowptr, 4 * (size_t)(no + 1), hipMemcpyHostToDevice));
+    if (n > 0) {
+        SL_HIP(L, hipMemcpy(L->colidx, colidx, 4 * (size_t)n, hipMemcpyHostToDevice));
+        SL_HIP(L, hipMemcpy(L->val, val, 4 * (size_t)n, hipMemcpyHostToDevice));
+        if (vel) SL_HIP(L, hipMemcpy(L->vel, vel, 4 * (size_t)n, hipMemcpyHostToDevice));
+        else SL_HIP(L, hipMemset(L->vel, 0, 4 * (size_t)n));
+    }
+    if (bias) SL_HIP(L, hipMemcpy(L->bias, bias, 4 * (size_t)no, hipMemcpyHostToDevice));
+    if (bias_vel) SL_HIP(L, hipMemcpy(L->bias_vel, bias_vel, 4 * (size_t)no, hipMemcpyHostToDevice));
+    int rc = topo_finalize(L, s);
+    if (rc) return rc;
+    SL_HIP(L, hipStreamSynchronize(s));
+    L->phase = 0;
+    return SL_OK;
+}
+
+int sparse_layer_export_grad(sl_layer *L, float *grad_val, float *grad_bias)
+{
+    if (!L) return SL_EINVAL;
+    if (L->phase < 2) return set_err(L, SL_ESTATE, "no gradient: backward has not run since the last update");
+    const size_t n = (size_t)L->nnz, no = (size_t)L->cfg.n_out;
+    int rc = SL_OK;
+    if (grad_val && n > 0) {
+        if (L->has_csc) {
+            // gradients live in CSC order; stage a CSR-ordered copy in scratch
+            float *tmp = (float *)(L->scratch + L->cp.s_val);
+            rc = topo_sync_csr_grad(L, tmp, L->last_stream);
+            if (!rc) rc = copy_out(L, grad_val, tmp, 4 * n);
+        } else {
+            rc = copy_out(L, grad_val, L->grad, 4 * n);
+        }
+    }
+    if (!rc) rc = copy_out(L, grad_bias, L->grad_bias, 4 * no);
+    if (rc) return rc;
+    SL_HIP(L, hipStreamSynchronize(L->last_stream));
+    return SL_OK;
+}
+
+int sparse_layer_set_lr(sl_layer *L, float lr)
+{
+    if (!L) return SL_EINVAL;
+    L->cfg.lr = lr;
+    return SL_OK;
+}
+
+const char *sparse_layer_last_error(const sl_layer *L) { return L ? L->err : "null layer"; }
+
+}  // extern "C"

@@ -1,0 +1,706 @@
+// Topology of a truly sparse layer on the GPU (gfx950): Erdos-Renyi initialisation, the SET
+// prune / regrow cycle of Algorithm 2 (radix-select threshold, prefix-sum compaction, Philox
+// counter-based regrowth, merge into a sorted CSR) and the derived structures (CSC view for the
+// backward pass, virtual-row tables).  Device-wide scans and radix sorts come from rocPRIM; every
+// other step is a kernel of this file.  All steps are deterministic: the resulting CSR depends
+// only on (pattern, weights, seed, layer_id, generation).
+#include <cstring>
+
+#include <rocprim/rocprim.hpp>
+
+#include "sl_internal.h"
+
+namespace sl {
+
+static constexpr int TB = 256;
+static inline unsigned nblk(long n) { return n <= 0 ? 1u : (unsigned)((n + TB - 1) / TB); }
+
+// ------------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11) and the stream layout of this library:
+// key = (lo32(seed) ^ layer_id*0x9E3779B9, hi32(seed)), counter = (index_lo, index_hi, purpose,
+// generation); purpose 1 = candidate position, 2 = dense-mode ordering key, 3 = weight value.
+// ------------------------------------------------------------------------------------------------
+struct Rng {
+    uint32_t k0, k1, generation;
+};
+
+__host__ __device__ inline void philox(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                       uint32_t out[4])
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t a = (uint64_t)0xD2511F53u * c0;
+        const uint64_t b = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(b >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(a >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)b;
+        c3 = (uint32_t)a;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+__device__ inline float fresh_weight(const Rng &r, uint64_t p, float limit)
+{
+    uint32_t o[4];
+    philox((uint32_t)p, (uint32_t)(p >> 32), 3u, r.generation, r.k0, r.k1, o);
+    const int odd = (int)(2u * (o[0] >> 9) + 1u) - (1 << 23);
+    return ((float)odd * (1.0f / 8388608.0f)) * limit;
+}
+
+// ------------------------------------------------------------------------------------------------
+// small search helpers
+// ------------------------------------------------------------------------------------------------
+__device__ inline int lower_bound_i32(const int *a, int lo, int hi, int x)
+{
+    while (lo < hi) {
+        const int mid = lo + ((hi - lo) >> 1);
+        if (a[mid] < x) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+__device__ inline long lower_bound_u64(const uint64_t *a, long n, uint64_t x)
+{
+    long lo = 0, hi = n;
+    while (lo < hi) {
+        const long mid = lo + ((hi - lo) >> 1);
+        if (a[mid] < x) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+// row that owns CSR position p: largest r with ptr[r] <= p
+__device__ inline int row_of(const int *ptr, int n_rows, int p)
+{
+    int lo = 0, hi = n_rows;   // invariant: ptr[lo] <= p < ptr[hi]
+    while (hi - lo > 1) {
+        const int mid = lo + ((hi - lo) >> 1);
+        if (ptr[mid] <= p) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// ------------------------------------------------------------------------------------------------
+// rocPRIM wrappers
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+static hipError_t scan_excl(void *temp, size_t temp_bytes, const T *in, T *out, size_t n, hipStream_t s)
+{
+    size_t need = temp_bytes;
+    return rocprim::exclusive_scan(temp, need, in, out, (T)0, n, rocprim::plus<T>(), s);
+}
+template <typename K>
+static hipError_t sort_pairs(void *temp, size_t temp_bytes, K *kA, K *kB, uint32_t *vA, uint32_t *vB, size_t n,
+                             unsigned bits, K **k_out, uint32_t **v_out, hipStream_t s)
+{
+    rocprim::double_buffer<K> kb(kA, kB);
+    rocprim::double_buffer<uint32_t> vb(vA, vB);
+    size_t need = temp_bytes;
+    hipError_t e = rocprim::radix_sort_pairs(temp, need, kb, vb, n, 0u, bits, s);
+    *k_out = kb.current();
+    *v_out = vb.current();
+    return e;
+}
+static unsigned bit_length(uint64_t x)
+{
+    unsigned b = 0;
+    while (x) { ++b; x >>= 1; }
+    return b ? b : 1;
+}
+
+int topo_check_temp(sl_layer *L, hipStream_t s)
+{
+    size_t need = 0, worst = 0;
+    const size_t n = (size_t)L->nnz + 1, w = (size_t)L->cp.w_cap + 1;
+    SL_HIP(L, rocprim::exclusive_scan(nullptr, need, (uint32_t *)nullptr, (uint32_t *)nullptr, 0u, w > n ? w : n,
+                                      rocprim::plus<uint32_t>(), s));
+    worst = need;
+    SL_HIP(L, rocprim::exclusive_scan(nullptr, need, (uint64_t *)nullptr, (uint64_t *)nullptr, (uint64_t)0, n,
+                                      rocprim::plus<uint64_t>(), s));
+    worst = need > worst ? need : worst;
+    {
+        rocprim::double_buffer<uint64_t> kb((uint64_t *)nullptr, (uint64_t *)nullptr);
+        rocprim::double_buffer<uint32_t> vb((uint32_t *)nullptr, (uint32_t *)nullptr);
+        SL_HIP(L, rocprim::radix_sort_pairs(nullptr, need, kb, vb, w, 0u, 64u, s));
+        worst = need > worst ? need : worst;
+    }
+    {
+        rocprim::double_buffer<uint32_t> kb((uint32_t *)nullptr, (uint32_t *)nullptr);
+        rocprim::double_buffer<uint32_t> vb((uint32_t *)nullptr, (uint32_t *)nullptr);
+        SL_HIP(L, rocprim::radix_sort_pairs(nullptr, need, kb, vb, n, 0u, 32u, s));
+        worst = need > worst ? need : worst;
+    }
+    if (worst > L->cp.temp_bytes)
+        return set_err(L, SL_ENOMEM, "rocPRIM temporaries need %zu bytes, %zu reserved", worst, L->cp.temp_bytes);
+    return SL_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Pruning threshold by radix select (four 8-bit passes, most significant digit first) on the
+// magnitude bits of the weights.  class 0 = all weights (mode 0) or weights >= 0 (mode 1),
+// class 1 = weights < 0 (mode 1 only).
+// ------------------------------------------------------------------------------------------------
+__device__ inline int weight_class(float w, int mode) { return (mode == 1 && w < 0.f) ? 1 : 0; }
+
+__global__ void class_count_kernel(const float *val, long n, uint32_t *counts)
+{
+    __shared__ uint32_t c;
+    if (threadIdx.x == 0) c = 0;
+    __syncthreads();
+    uint32_t mine = 0;
+    for (long p = (long)blockIdx.x * TB + threadIdx.x; p < n; p += (long)gridDim.x * TB) mine += val[p] < 0.f;
+    // wavefront-level reduction, one atomic per wavefront
+    for (int m = 32; m >= 1; m >>= 1) mine += __shfl_xor(mine, m);
+    if ((threadIdx.x & 63) == 0) atomicAdd(&c, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) atomicAdd(&counts[0], c);
+}
+
+__global__ void select_setup_kernel(SelState *st, uint32_t k0, uint32_t k1)
+{
+    const int c = blockIdx.x;
+    SelState &s = st[c];
+    if (threadIdx.x == 0) {
+        const uint32_t k = c == 0 ? k0 : k1;
+        s.prefix = 0; s.krem = k; s.active = k > 0; s.thresh = 0; s.need = 0;
+    }
+    s.hist[threadIdx.x] = 0;
+}
+
+__global__ void select_hist_kernel(const float *val, long n, int mode, int shift, SelState *st)
+{
+    __shared__ uint32_t h[2][256];
+    h[0][threadIdx.x] = 0;
+    h[1][threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t act0 = st[0].active, act1 = st[1].active;
+    const uint32_t pre0 = st[0].prefix, pre1 = st[1].prefix;
+    for (long p = (long)blockIdx.x * TB + threadIdx.x; p < n; p += (long)gridDim.x * TB) {
+        const float w = val[p];
+        const int c = weight_class(w, mode);
+        const uint32_t mag = __float_as_uint(w) & 0x7FFFFFFFu;
+        const uint32_t act = c ? act1 : act0, pre = c ? pre1 : pre0;
+        const bool in = act && (shift == 24 || (mag >> (shift + 8)) == pre);
+        if (in) atomicAdd(&h[c][(mag >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (h[0][threadIdx.x]) atomicAdd(&st[0].hist[threadIdx.x], h[0][threadIdx.x]);
+    if (h[1][threadIdx.x]) atomicAdd(&st[1].hist[threadIdx.x], h[1][threadIdx.x]);
+}
+
+// picks the digit that contains the krem-th smallest remaining key; on the last pass the prefix is
+// the threshold and krem the number of entries equal to it that still have to go.
+__global__ void select_pick_kernel(SelState *st, int last)
+{
+    SelState &s = st[blockIdx.x];
+    if (threadIdx.x == 0 && s.active) {
+        uint32_t cum = 0;
+        int d = 0;
+        for (; d < 255; ++d) {
+            if (cum + s.hist[d] >= s.krem) break;
+            cum += s.hist[d];
+        }
+        s.krem -= cum;
+        s.prefix = (s.prefix << 8) | (uint32_t)d;
+        if (last) { s.thresh = s.prefix; s.need = s.krem; }
+    }
+    __syncthreads();
+    s.hist[threadIdx.x] = 0;
+}
+
+// tie[p] = 1 in the low (class 0) or high (class 1) half iff |val[p]| equals its class threshold
+__global__ void tie_flag_kernel(const float *val, long n, int mode, const SelState *st, uint64_t *tie)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p > n) return;
+    uint64_t t = 0;
+    if (p < n) {
+        const float w = val[p];
+        const int c = weight_class(w, mode);
+        const uint32_t mag = __float_as_uint(w) & 0x7FFFFFFFu;
+        if (st[c].active && mag == st[c].thresh) t = c ? (1ull << 32) : 1ull;
+    }
+    tie[p] = t;
+}
+
+// keep[p] = 0 iff the entry is among the removed ones: magnitude below the threshold, or equal to
+// it and among the first `need` such entries in CSR order (= smallest flat positions).
+__global__ void keep_flag_kernel(const float *val, long n, int mode, const SelState *st, const uint64_t *trank,
+                                 uint32_t *keep)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p > n) return;
+    uint32_t k = 0;
+    if (p < n) {
+        const float w = val[p];
+        const int c = weight_class(w, mode);
+        const uint32_t mag = __float_as_uint(w) & 0x7FFFFFFFu;
+        bool gone = false;
+        if (st[c].active) {
+            const uint32_t rank = c ? (uint32_t)(trank[p] >> 32) : (uint32_t)trank[p];
+            gone = mag < st[c].thresh || (mag == st[c].thresh && rank < st[c].need);
+        }
+        k = gone ? 0u : 1u;
+    }
+    keep[p] = k;
+}
+
+__global__ void compact_kernel(long n, const uint32_t *keep, const uint32_t *kscan, const int *col, const float *val,
+                               const float *vel, int *s_col, float *s_val, float *s_vel)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p >= n || !keep[p]) return;
+    const uint32_t d = kscan[p];
+    s_col[d] = col[p];
+    s_val[d] = val[p];
+    s_vel[d] = vel[p];
+}
+
+__global__ void survivor_rowptr_kernel(int n_rows, const int *rowptr, const uint32_t *kscan, int *rowptr_s)
+{
+    const int r = blockIdx.x * TB + threadIdx.x;
+    if (r > n_rows) return;
+    rowptr_s[r] = (int)kscan[rowptr[r]];   // kscan has n+1 entries; kscan[n] = number of survivors
+}
+
+// ------------------------------------------------------------------------------------------------
+// Sampler: k distinct empty positions.
+// sparse mode: candidate t -> position (row, col) from Philox(purpose 1, index t); a candidate is
+//   accepted iff it is not occupied and no earlier candidate had the same position; the first k
+//   accepted candidates (in t order) are the result.  Evaluated for a whole window of t at once:
+//   stable sort by position, first-of-run + not-occupied test, prefix count in t order.
+// dense mode: every empty position gets a 64-bit Philox ordering key (purpose 2); the k smallest
+//   (key, position) are the result.
+// ------------------------------------------------------------------------------------------------
+__global__ void cand_kernel(long W, Rng r, uint32_t n_in, uint32_t n_out, uint64_t *key, uint32_t *pay)
+{
+    const long t = (long)blockIdx.x * TB + threadIdx.x;
+    if (t >= W) return;
+    uint32_t o[4];
+    philox((uint32_t)t, (uint32_t)((uint64_t)t >> 32), 1u, r.generation, r.k0, r.k1, o);
+    const uint64_t j = ((uint64_t)o[0] * n_out) >> 32;
+    const uint64_t i = ((uint64_t)o[1] * n_in) >> 32;
+    key[t] = j * n_in + i;
+    pay[t] = (uint32_t)t;
+}
+
+__device__ inline bool occupied(const int *rowptr_s, const int *s_col, uint32_t n_in, uint64_t p)
+{
+    const int j = (int)(p / n_in), i = (int)(p % n_in);
+    const int lo = rowptr_s[j], hi = rowptr_s[j + 1];
+    const int q = lower_bound_i32(s_col, lo, hi, i);
+    return q < hi && s_col[q] == i;
+}
+
+// in sorted order: ok = first of its run and not occupied; scattered to t order as well
+__global__ void cand_ok_kernel(long W, const uint64_t *key, const uint32_t *pay, const int *rowptr_s,
+                               const int *s_col, uint32_t n_in, uint32_t *ok_sorted, uint32_t *ok_by_t)
+{
+    const long x = (long)blockIdx.x * TB + threadIdx.x;
+    if (x > W) return;
+    if (x == W) { ok_sorted[W] = 0; ok_by_t[W] = 0; return; }
+    const uint64_t p = key[x];
+    const bool ok = (x == 0 || key[x - 1] != p) && !occupied(rowptr_s, s_col, n_in, p);
+    ok_sorted[x] = ok;
+    ok_by_t[pay[x]] = ok;
+}
+
+// in sorted order: selected = ok and fewer than k accepted candidates precede it in t order
+__global__ void cand_select_kernel(long W, const uint32_t *pay, const uint32_t *rank_by_t, uint32_t k,
+                                   uint32_t *ok_sorted)
+{
+    const long x = (long)blockIdx.x * TB + threadIdx.x;
+    if (x >= W) return;
+    ok_sorted[x] = (ok_sorted[x] && rank_by_t[pay[x]] < k) ? 1u : 0u;
+}
+
+__global__ void gather_selected_kernel(long W, const uint32_t *sel, const uint32_t *sscan, const uint64_t *key,
+                                       uint64_t *new_p)
+{
+    const long x = (long)blockIdx.x * TB + threadIdx.x;
+    if (x >= W || !sel[x]) return;
+    new_p[sscan[x]] = key[x];
+}
+
+// dense mode
+__global__ void empty_flag_kernel(long M, const int *rowptr_s, const int *s_col, uint32_t n_in, uint32_t *flag)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p > M) return;
+    flag[p] = (p < M && !occupied(rowptr_s, s_col, n_in, (uint64_t)p)) ? 1u : 0u;
+}
+__global__ void empty_key_kernel(long M, const uint32_t *flag, const uint32_t *fscan, Rng r, uint64_t *key,
+                                 uint32_t *pay)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p >= M || !flag[p]) return;
+    uint32_t o[4];
+    philox((uint32_t)p, (uint32_t)((uint64_t)p >> 32), 2u, r.generation, r.k0, r.k1, o);
+    const uint32_t d = fscan[p];
+    key[d] = ((uint64_t)o[0] << 32) | o[1];
+    pay[d] = (uint32_t)p;
+}
+__global__ void zero_u32_kernel(long n, uint32_t *a)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p < n) a[p] = 0;
+}
+__global__ void mark_chosen_kernel(long k, const uint32_t *pay_sorted, uint32_t *flag)
+{
+    const long x = (long)blockIdx.x * TB + threadIdx.x;
+    if (x < k) flag[pay_sorted[x]] = 1u;
+}
+__global__ void gather_marked_kernel(long M, const uint32_t *flag, const uint32_t *fscan, uint64_t *new_p)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p >= M || !flag[p]) return;
+    new_p[fscan[p]] = (uint64_t)p;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Merge survivors (CSR order) and the sorted new positions into the final CSR.
+// ------------------------------------------------------------------------------------------------
+__global__ void merge_rowptr_kernel(int n_rows, uint32_t n_in, const int *rowptr_s, const uint64_t *new_p, long k,
+                                    int *rowptr)
+{
+    const int r = blockIdx.x * TB + threadIdx.x;
+    if (r > n_rows) return;
+    rowptr[r] = rowptr_s[r] + (int)lower_bound_u64(new_p, k, (uint64_t)r * n_in);
+}
+__global__ void merge_survivor_kernel(long ns, int n_rows, uint32_t n_in, const int *rowptr_s, const int *s_col,
+                                      const float *s_val, const float *s_vel, const uint64_t *new_p, long k,
+                                      int *col, float *val, float *vel)
+{
+    const long s = (long)blockIdx.x * TB + threadIdx.x;
+    if (s >= ns) return;
+    const int j = row_of(rowptr_s, n_rows, (int)s);
+    const int i = s_col[s];
+    const long d = s + lower_bound_u64(new_p, k, (uint64_t)j * n_in + (uint64_t)i);
+    col[d] = i;
+    val[d] = s_val[s];
+    vel[d] = s_vel[s];
+}
+__global__ void merge_new_kernel(long k, uint32_t n_in, const int *rowptr_s, const int *s_col, const uint64_t *new_p,
+                                 Rng r, float limit, int *col, float *val, float *vel)
+{
+    const long t = (long)blockIdx.x * TB + threadIdx.x;
+    if (t >= k) return;
+    const uint64_t p = new_p[t];
+    const int j = (int)(p / n_in), i = (int)(p % n_in);
+    const long d = t + lower_bound_i32(s_col, rowptr_s[j], rowptr_s[j + 1], i);
+    col[d] = i;
+    val[d] = fresh_weight(r, p, limit);
+    vel[d] = 0.f;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Derived structures
+// ------------------------------------------------------------------------------------------------
+__global__ void max_len_kernel(int n_rows, const int *ptr, int *out)
+{
+    int m = 0;
+    for (long r = (long)blockIdx.x * TB + threadIdx.x; r < n_rows; r += (long)gridDim.x * TB)
+        m = max(m, ptr[r + 1] - ptr[r]);
+    for (int s = 32; s >= 1; s >>= 1) m = max(m, __shfl_xor(m, s));
+    if ((threadIdx.x & 63) == 0) atomicMax(out, m);
+}
+__global__ void vcount_kernel(int n_rows, const int *ptr, int seg, uint32_t *cnt)
+{
+    const int r = blockIdx.x * TB + threadIdx.x;
+    if (r > n_rows) return;
+    uint32_t c = 0;
+    if (r < n_rows) {
+        const int len = ptr[r + 1] - ptr[r];
+        c = len <= seg ? 1u : (uint32_t)((len + seg - 1) / seg);
+    }
+    cnt[r] = c;
+}
+__global__ void vfill_kernel(int n_rows, const int *ptr, int seg, const int *rvptr, int *vptr, int *v2row, int nnz)
+{
+    const int r = blockIdx.x * TB + threadIdx.x;
+    if (r > n_rows) return;
+    if (r == n_rows) { vptr[rvptr[n_rows]] = nnz; return; }
+    const int v0 = rvptr[r], v1 = rvptr[r + 1];
+    for (int v = v0; v < v1; ++v) {
+        vptr[v] = ptr[r] + (v - v0) * seg;
+        v2row[v] = r;
+    }
+}
+__global__ void iota_copy_kernel(long n, const int *col, uint32_t *key, uint32_t *pay)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p >= n) return;
+    key[p] = (uint32_t)col[p];
+    pay[p] = (uint32_t)p;
+}
+__global__ void colptr_kernel(int n_cols, const uint32_t *key_sorted, long n, int *colptr)
+{
+    const int c = blockIdx.x * TB + threadIdx.x;
+    if (c > n_cols) return;
+    long lo = 0, hi = n;
+    while (lo < hi) {
+        const long mid = lo + ((hi - lo) >> 1);
+        if (key_sorted[mid] < (uint32_t)c) lo = mid + 1; else hi = mid;
+    }
+    colptr[c] = (int)lo;
+}
+__global__ void csc_fill_kernel(long n, int n_rows, const int *rowptr, const uint32_t *pos_sorted, const float *val,
+                                const float *vel, int *rowidx, int *csr_pos, float *valT, float *velT)
+{
+    const long q = (long)blockIdx.x * TB + threadIdx.x;
+    if (q >= n) return;
+    const int p = (int)pos_sorted[q];
+    csr_pos[q] = p;
+    rowidx[q] = row_of(rowptr, n_rows, p);
+    valT[q] = val[p];
+    velT[q] = vel[p];
+}
+__global__ void scatter_f32_kernel(long n, const int *pos, const float *src, float *dst)
+{
+    const long q = (long)blockIdx.x * TB + threadIdx.x;
+    if (q < n) dst[pos[q]] = src[q];
+}
+__global__ void fill_f32_kernel(long n, float *a, float v)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p < n) a[p] = v;
+}
+__global__ void fill_i32_kernel(long n, int *a, int v)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p < n) a[p] = v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// host orchestration
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+static T *at(sl_layer *L, size_t off) { return reinterpret_cast<T *>(L->scratch + off); }
+
+static int read_back(sl_layer *L, void *host, const void *dev, size_t bytes, hipStream_t s)
+{
+    SL_HIP(L, hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, s));
+    SL_HIP(L, hipStreamSynchronize(s));
+    return SL_OK;
+}
+
+static Rng make_rng(const sl_layer *L, uint32_t generation)
+{
+    Rng r;
+    r.k0 = (uint32_t)L->cfg.seed ^ (uint32_t)(L->cfg.layer_id * 0x9E3779B9u);
+    r.k1 = (uint32_t)(L->cfg.seed >> 32);
+    r.generation = generation;
+    return r;
+}
+
+static int build_vrows(sl_layer *L, SegMat &m, int nnz, hipStream_t s)
+{
+    int *small = at<int>(L, L->cp.small);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(TB), 0, s, 1L, small, 0);
+    hipLaunchKernelGGL(max_len_kernel, dim3(std::min(1024u, nblk(m.n_rows))), dim3(TB), 0, s, m.n_rows, m.ptr, small);
+    int maxlen = 0;
+    int rc = read_back(L, &maxlen, small, sizeof(int), s);
+    if (rc) return rc;
+    m.seg = choose_seg(m.n_rows, nnz);
+    if (maxlen <= m.seg) {
+        m.split = 0; m.vptr = m.ptr; m.v2row = nullptr; m.rvptr = nullptr; m.nv = m.n_rows;
+        return SL_OK;
+    }
+    uint32_t *cnt = at<uint32_t>(L, L->cp.f0);
+    hipLaunchKernelGGL(vcount_kernel, dim3(nblk(m.n_rows + 1)), dim3(TB), 0, s, m.n_rows, m.ptr, m.seg, cnt);
+    SL_HIP(L, scan_excl<uint32_t>(at<char>(L, L->cp.temp), L->cp.temp_bytes, cnt, (uint32_t *)m.rvptr_store,
+                                  (size_t)m.n_rows + 1, s));
+    int nv = 0;
+    rc = read_back(L, &nv, m.rvptr_store + m.n_rows, sizeof(int), s);
+    if (rc) return rc;
+    if (nv > m.nv_cap) return set_err(L, SL_ENOMEM, "virtual rows %d exceed capacity %d", nv, m.nv_cap);
+    hipLaunchKernelGGL(vfill_kernel, dim3(nblk(m.n_rows + 1)), dim3(TB), 0, s, m.n_rows, m.ptr, m.seg, m.rvptr_store,
+                       m.vptr_store, m.v2row_store, nnz);
+    m.split = 1; m.vptr = m.vptr_store; m.v2row = m.v2row_store; m.rvptr = m.rvptr_store; m.nv = nv;
+    SL_HIP(L, hipGetLastError());
+    return SL_OK;
+}
+
+int topo_finalize(sl_layer *L, hipStream_t s)
+{
+    const int n = (int)L->nnz, n_in = (int)L->cfg.n_in, n_out = (int)L->cfg.n_out;
+    L->fwd.n_rows = n_out; L->fwd.ptr = L->rowptr; L->fwd.idx = L->colidx;
+    int rc = build_vrows(L, L->fwd, n, s);
+    if (rc) return rc;
+    if (!L->has_csc) return SL_OK;
+    // CSC view: stable sort of (column, CSR position) keeps rows ascending inside a column
+    uint32_t *kA = at<uint32_t>(L, L->cp.keyA), *kB = at<uint32_t>(L, L->cp.keyB);
+    uint32_t *vA = at<uint32_t>(L, L->cp.payA), *vB = at<uint32_t>(L, L->cp.payB);
+    uint32_t *ks = kA, *vs = vA;
+    if (n > 0) {
+        hipLaunchKernelGGL(iota_copy_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, L->colidx, kA, vA);
+        SL_HIP(L, sort_pairs<uint32_t>(at<char>(L, L->cp.temp), L->cp.temp_bytes, kA, kB, vA, vB, (size_t)n,
+                                       bit_length((uint64_t)n_in - 1), &ks, &vs, s));
+        hipLaunchKernelGGL(csc_fill_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, n_out, L->rowptr, vs, L->val,
+                           L->vel, L->rowidx, L->csr_pos, L->valT, L->velT);
+    }
+    hipLaunchKernelGGL(colptr_kernel, dim3(nblk(n_in + 1)), dim3(TB), 0, s, n_in, ks, (long)n, L->colptr);
+    SL_HIP(L, hipGetLastError());
+    L->bwd.n_rows = n_in; L->bwd.ptr = L->colptr; L->bwd.idx = L->rowidx;
+    return build_vrows(L, L->bwd, n, s);
+}
+
+int topo_sync_csr_vel(sl_layer *L, hipStream_t s)
+{
+    if (!L->has_csc || L->nnz == 0) return SL_OK;
+    hipLaunchKernelGGL(scatter_f32_kernel, dim3(nblk(L->nnz)), dim3(TB), 0, s, (long)L->nnz, L->csr_pos, L->velT, L->vel);
+    SL_HIP(L, hipGetLastError());
+    return SL_OK;
+}
+
+int topo_sync_csr_grad(sl_layer *L, float *grad_csr_dev, hipStream_t s)
+{
+    if (L->nnz == 0) return SL_OK;
+    hipLaunchKernelGGL(scatter_f32_kernel, dim3(nblk(L->nnz)), dim3(TB), 0, s, (long)L->nnz, L->csr_pos, L->grad,
+                       grad_csr_dev);
+    SL_HIP(L, hipGetLastError());
+    return SL_OK;
+}
+
+// Draws k distinct positions that are empty w.r.t. the survivors (rowptr_s, s_col) into new_p,
+// ascending.  n_occ = number of survivors.
+static int sample_positions(sl_layer *L, long k, long n_occ, uint32_t generation, hipStream_t s)
+{
+    if (k == 0) return SL_OK;
+    const uint32_t n_in = (uint32_t)L->cfg.n_in, n_out = (uint32_t)L->cfg.n_out;
+    const uint64_t M = (uint64_t)n_in * n_out;
+    const Rng r = make_rng(L, generation);
+    const int *rowptr_s = at<int>(L, L->cp.rowptr_s), *s_col = at<int>(L, L->cp.s_col);
+    uint64_t *kA = at<uint64_t>(L, L->cp.keyA), *kB = at<uint64_t>(L, L->cp.keyB);
+    uint32_t *vA = at<uint32_t>(L, L->cp.payA), *vB = at<uint32_t>(L, L->cp.payB);
+    uint32_t *f0 = at<uint32_t>(L, L->cp.f0), *f1 = at<uint32_t>(L, L->cp.f1);
+    uint32_t *f2 = at<uint32_t>(L, L->cp.f2), *f3 = at<uint32_t>(L, L->cp.f3);
+    uint64_t *new_p = at<uint64_t>(L, L->cp.new_p);
+    char *temp = at<char>(L, L->cp.temp);
+    uint64_t *ks; uint32_t *vs;
+    if (L->cp.dense_mode) {
+        const long Ml = (long)M;
+        hipLaunchKernelGGL(empty_flag_kernel, dim3(nblk(Ml + 1)), dim3(TB), 0, s, Ml, rowptr_s, s_col, n_in, f0);
+        SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, f0, f1, (size_t)Ml + 1, s));
+        hipLaunchKernelGGL(empty_key_kernel, dim3(nblk(Ml)), dim3(TB), 0, s, Ml, f0, f1, r, kA, vA);
+        const long n_empty = Ml - n_occ;
+        SL_HIP(L, sort_pairs<uint64_t>(temp, L->cp.temp_bytes, kA, kB, vA, vB, (size_t)n_empty, 64u, &ks, &vs, s));
+        hipLaunchKernelGGL(zero_u32_kernel, dim3(nblk(Ml + 1)), dim3(TB), 0, s, Ml + 1, f2);
+        hipLaunchKernelGGL(mark_chosen_kernel, dim3(nblk(k)), dim3(TB), 0, s, k, vs, f2);
+        SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, f2, f3, (size_t)Ml + 1, s));
+        hipLaunchKernelGGL(gather_marked_kernel, dim3(nblk(Ml)), dim3(TB), 0, s, Ml, f2, f3, new_p);
+        SL_HIP(L, hipGetLastError());
+        return SL_OK;
+    }
+    long W = sampler_window((double)M, (double)n_occ, (double)k);
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        if (W > L->cp.w_cap) W = L->cp.w_cap;
+        hipLaunchKernelGGL(cand_kernel, dim3(nblk(W)), dim3(TB), 0, s, W, r, n_in, n_out, kA, vA);
+        SL_HIP(L, sort_pairs<uint64_t>(temp, L->cp.temp_bytes, kA, kB, vA, vB, (size_t)W, bit_length(M - 1), &ks, &vs, s));
+        hipLaunchKernelGGL(cand_ok_kernel, dim3(nblk(W + 1)), dim3(TB), 0, s, W, ks, vs, rowptr_s, s_col, n_in, f0, f1);
+        SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, f1, f2, (size_t)W + 1, s));
+        uint32_t accepted = 0;
+        int rc = read_back(L, &accepted, f2 + W, sizeof(uint32_t), s);
+        if (rc) return rc;
+        if ((long)accepted >= k) {
+            hipLaunchKernelGGL(cand_select_kernel, dim3(nblk(W)), dim3(TB), 0, s, W, vs, f2, (uint32_t)k, f0);
+            SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, f0, f3, (size_t)W + 1, s));
+            hipLaunchKernelGGL(gather_selected_kernel, dim3(nblk(W)), dim3(TB), 0, s, W, f0, f3, ks, new_p);
+            SL_HIP(L, hipGetLastError());
+            return SL_OK;
+        }
+        if (W == L->cp.w_cap) break;
+        W *= 2;
+    }
+    return set_err(L, SL_ESTATE, "position sampler: window exhausted before %ld positions were accepted", k);
+}
+
+// survivors (ns of them, in scratch) + k new connections at `generation` -> CSR arrays of L
+static int rebuild(sl_layer *L, long ns, long k, uint32_t generation, hipStream_t s)
+{
+    const int n_out = (int)L->cfg.n_out;
+    const uint32_t n_in = (uint32_t)L->cfg.n_in;
+    int rc = sample_positions(L, k, ns, generation, s);
+    if (rc) return rc;
+    const int *rowptr_s = at<int>(L, L->cp.rowptr_s), *s_col = at<int>(L, L->cp.s_col);
+    const float *s_val = at<float>(L, L->cp.s_val), *s_vel = at<float>(L, L->cp.s_vel);
+    const uint64_t *new_p = at<uint64_t>(L, L->cp.new_p);
+    hipLaunchKernelGGL(merge_rowptr_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, n_out, n_in, rowptr_s, new_p, k,
+                       L->rowptr);
+    if (ns > 0)
+        hipLaunchKernelGGL(merge_survivor_kernel, dim3(nblk(ns)), dim3(TB), 0, s, ns, n_out, n_in, rowptr_s, s_col,
+                           s_val, s_vel, new_p, k, L->colidx, L->val, L->vel);
+    if (k > 0)
+        hipLaunchKernelGGL(merge_new_kernel, dim3(nblk(k)), dim3(TB), 0, s, k, n_in, rowptr_s, s_col, new_p,
+                           make_rng(L, generation), L->cfg.init_limit, L->colidx, L->val, L->vel);
+    SL_HIP(L, hipGetLastError());
+    return topo_finalize(L, s);
+}
+
+int topo_init(sl_layer *L, hipStream_t s)
+{
+    const int n_out = (int)L->cfg.n_out;
+    int rc = topo_check_temp(L, s);
+    if (rc) return rc;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, (long)n_out + 1,
+                       at<int>(L, L->cp.rowptr_s), 0);
+    hipLaunchKernelGGL(fill_f32_kernel, dim3(nblk(n_out)), dim3(TB), 0, s, (long)n_out, L->bias, 0.f);
+    hipLaunchKernelGGL(fill_f32_kernel, dim3(nblk(n_out)), dim3(TB), 0, s, (long)n_out, L->bias_vel, 0.f);
+    hipLaunchKernelGGL(fill_f32_kernel, dim3(nblk(n_out)), dim3(TB), 0, s, (long)n_out, L->grad_bias, 0.f);
+    if (L->nnz > 0) hipLaunchKernelGGL(fill_f32_kernel, dim3(nblk(L->nnz)), dim3(TB), 0, s, (long)L->nnz, L->grad, 0.f);
+    SL_HIP(L, hipGetLastError());
+    return rebuild(L, 0, L->nnz, 0u, s);
+}
+
+int topo_evolve(sl_layer *L, double zeta, uint32_t generation, hipStream_t s)
+{
+    const long n = L->nnz;
+    const int n_out = (int)L->cfg.n_out;
+    const int mode = L->cfg.prune_mode;
+    int rc = topo_sync_csr_vel(L, s);
+    if (rc) return rc;
+    // number of removals per class, floor(zeta*count + 0.5) in double
+    long cnt[2] = {n, 0};
+    if (mode == 1) {
+        uint32_t *small = at<uint32_t>(L, L->cp.small);
+        hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(TB), 0, s, 1L, small);
+        if (n > 0) hipLaunchKernelGGL(class_count_kernel, dim3(std::min(1024u, nblk(n))), dim3(TB), 0, s, L->val, n, small);
+        uint32_t neg = 0;
+        rc = read_back(L, &neg, small, sizeof(uint32_t), s);
+        if (rc) return rc;
+        cnt[1] = neg; cnt[0] = n - neg;
+    }
+    long kc[2];
+    for (int c = 0; c < 2; ++c) {
+        kc[c] = (long)floor(zeta * (double)cnt[c] + 0.5);
+        if (kc[c] < 0) kc[c] = 0;
+        if (kc[c] > cnt[c]) kc[c] = cnt[c];
+    }
+    const long k = kc[0] + kc[1];
+    if (k == 0) return SL_OK;
+    hipLaunchKernelGGL(select_setup_kernel, dim3(2), dim3(256), 0, s, L->sel, (uint32_t)kc[0], (uint32_t)kc[1]);
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hipLaunchKernelGGL(select_hist_kernel, dim3(std::min(2048u, nblk(n))), dim3(TB), 0, s, L->val, n, mode, shift, L->sel);
+        hipLaunchKernelGGL(select_pick_kernel, dim3(2), dim3(256), 0, s, L->sel, shift == 0 ? 1 : 0);
+    }
+    uint64_t *tie = at<uint64_t>(L, L->cp.tie64), *trank = at<uint64_t>(L, L->cp.trank);
+    uint32_t *keep = at<uint32_t>(L, L->cp.keep), *kscan = at<uint32_t>(L, L->cp.kscan);
+    char *temp = at<char>(L, L->cp.temp);
+    hipLaunchKernelGGL(tie_flag_kernel, dim3(nblk(n + 1)), dim3(TB), 0, s, L->val, n, mode, L->sel, tie);
+    SL_HIP(L, scan_excl<uint64_t>(temp, L->cp.temp_bytes, tie, trank, (size_t)n + 1, s));
+    hipLaunchKernelGGL(keep_flag_kernel, dim3(nblk(n + 1)), dim3(TB), 0, s, L->val, n, mode, L->sel, trank, keep);
+    SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, keep, kscan, (size_t)n + 1, s));
+    hipLaunchKernelGGL(compact_kernel, dim3(nblk(n)), dim3(TB), 0, s, n, keep, kscan, L->colidx, L->val, L->vel,
+                       at<int>(L, L->cp.s_col), at<float>(L, L->cp.s_val), at<float>(L, L->cp.s_vel));
+    hipLaunchKernelGGL(survivor_rowptr_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, n_out, L->rowptr, kscan,
+                       at<int>(L, L->cp.rowptr_s));
+    uint32_t kept = 0;
+    rc = read_back(L, &kept, kscan + n, sizeof(uint32_t), s);
+    if (rc) return rc;
+    if ((long)kept != n - k) return set_err(L, SL_ESTATE, "prune kept %u entries, expected %ld", kept, n - k);
+    return rebuild(L, n - k, k, generation, s);
+}
+
+}  // namespace sl

@@ -1,0 +1,283 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on
+the same seeded inputs.  Topology, indices and counts must be bit-exact; fp32 tensors must agree
+within relative 1e-4 after one step and 1e-3 after an epoch (normwise, and max-abs relative to the
+largest oracle magnitude)."""
+import numpy as np
+import pytest
+
+from paper_2102_01732_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2102_01732_amd import binding
+    binding.lib()
+    return binding
+
+
+def close(got, ref, tol, what=""):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, what
+    assert np.all(np.isfinite(got)), what
+    scale = np.abs(ref).max()
+    if scale == 0:
+        assert np.abs(got).max() == 0, what
+        return
+    err = np.abs(got - ref).max()
+    assert err <= tol * scale, f"{what}: max abs err {err:.3e} > {tol} * {scale:.3e}"
+    nrm = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    assert nrm <= tol, f"{what}: normwise err {nrm:.3e} > {tol}"
+
+
+def dev(t, arr):
+    return t.from_numpy(np.ascontiguousarray(arr)).to("cuda:0")
+
+
+def pad_cols(arr, ld):
+    out = np.full((arr.shape[0], ld), np.nan, dtype=np.float32)   # padding must never be read as data
+    out[:, : arr.shape[1]] = arr
+    return out
+
+
+def make_pair(gpu, oracle, n_in, n_out, nnz, *, act_kind=1, parity=0, alpha=0.6, limit=0.3, seed=11, layer_id=2,
+              max_batch=128, prune_mode=0, need_input_grad=True, lr=0.01, mu=0.9):
+    cfg = gpu.make_config(n_in, n_out, nnz=nnz, act_kind=act_kind, act_parity=parity, alpha=alpha, init_limit=limit,
+                          lr=lr, momentum=mu, seed=seed, layer_id=layer_id, max_batch=max_batch,
+                          prune_mode=prune_mode, need_input_grad=need_input_grad)
+    G = gpu.SparseLayer(cfg)
+    O = oracle.OracleLayer(n_in, n_out, nnz, act_kind, parity, alpha, limit, lr, mu, 0.0, seed, layer_id, prune_mode)
+    return G, O
+
+
+def assert_same_topology(G, O, values=True):
+    rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+    assert np.array_equal(rowptr, O.rowptr)
+    assert np.array_equal(colidx, O.colidx)
+    if values:
+        assert np.array_equal(val.view(np.uint32), O.val.view(np.uint32))
+        assert np.array_equal(vel.view(np.uint32), O.vel.view(np.uint32))
+
+
+# ------------------------------------------------------------------------------------------ init
+@pytest.mark.parametrize("n_in,n_out,nnz", [
+    (500, 400, 9000), (400, 100, 5000),      # sparse sampler mode
+    (400, 2, 800), (1000, 10, 10000),        # fully dense output layers (dense sampler mode)
+    (64, 48, 1000),                          # dense mode, not full
+    (3000, 5000, 37), (7, 5, 0), (1, 1, 1),  # nearly empty / empty / single
+    (100000, 70000, 1700000)])               # several sort tiles, 64-bit flat positions > 2^32
+def test_init_topology_bit_exact(gpu, oracle, n_in, n_out, nnz):
+    G, O = make_pair(gpu, oracle, n_in, n_out, nnz)
+    assert G.nnz == nnz == O.nnz
+    assert_same_topology(G, O)
+    rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+    assert np.all(vel == 0) and np.all(bias == 0) and np.all(bias_vel == 0)
+    G.close()
+
+
+# ------------------------------------------------------------------------------------------ one layer, one step
+@pytest.mark.parametrize("n_in,n_out,nnz,B,max_batch,act_kind,parity,need_gx", [
+    (500, 400, 9000, 128, 128, 1, 0, True),
+    (500, 400, 9000, 128, 128, 1, 1, False),
+    (300, 700, 6000, 96, 128, 1, 0, True),        # partial last minibatch
+    (300, 700, 6000, 5, 128, 1, 1, True),         # ragged: not a multiple of 4
+    (300, 700, 6000, 31, 32, 1, 0, True),         # G = 8 path, ragged
+    (256, 300, 4000, 64, 64, 1, 0, True),         # G = 16 path
+    (200, 150, 3000, 200, 256, 1, 1, True),       # G = 64 path
+    (200, 150, 3000, 300, 512, 1, 0, True),       # two batch tiles of 256 columns, ragged tail
+    (200, 150, 3000, 299, 512, 1, 0, False),      # SDDMM-only path, tiles + ragged
+    (400, 2, 800, 128, 128, 0, 0, True),          # dense output layer: long rows are split
+    (3000, 10, 30000, 80, 128, 0, 0, True),       # dense output layer, rows of 3000
+    (6, 2000, 12000, 128, 128, 1, 0, True),       # long columns: the CSC side is split
+    (3000, 5000, 37, 128, 128, 1, 0, True),       # mostly empty rows and columns
+    (2000, 3000, 90000, 128, 128, 1, 0, True)])
+def test_forward_backward_update_one_layer(gpu, oracle, n_in, n_out, nnz, B, max_batch, act_kind, parity, need_gx):
+    import torch
+    G, O = make_pair(gpu, oracle, n_in, n_out, nnz, act_kind=act_kind, parity=parity, max_batch=max_batch,
+                     need_input_grad=need_gx, limit=0.2)
+    assert_same_topology(G, O)
+    rng = np.random.default_rng(n_in + B)
+    # non-zero bias and velocity so that every term of the formulas is exercised
+    rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+    vel = (rng.standard_normal(nnz) * 0.01).astype(np.float32)
+    bias = (rng.standard_normal(n_out) * 0.1).astype(np.float32)
+    bias_vel = (rng.standard_normal(n_out) * 0.01).astype(np.float32)
+    G.import_csr(rowptr, colidx, val, vel, bias, bias_vel)
+    O.set_state(rowptr, colidx, val, vel, bias, bias_vel)
+    ld = (B + 3) // 4 * 4 + 4
+    x = rng.standard_normal((n_in, B)).astype(np.float32)
+    ga = rng.standard_normal((n_out, B)).astype(np.float32)
+    xd, gad = dev(torch, pad_cols(x, ld)), dev(torch, pad_cols(ga, ld))
+    ad = torch.full((n_out, ld), 7.0, dtype=torch.float32, device="cuda:0")
+    gxd = torch.full((n_in, ld), 7.0, dtype=torch.float32, device="cuda:0") if need_gx else None
+    # oracle
+    a_ref = O.forward(x)
+    assert np.abs(O.z).min() > 1e-6 or act_kind == 0, "seed puts a pre-activation on the kink"
+    gx_ref = O.backward(x, ga, need_input_grad=need_gx)
+    # GPU
+    G.forward(xd, B, ad)
+    G.backward(xd, gad, B, gxd)
+    g, gb = G.export_grad()
+    torch.cuda.synchronize()
+    a = ad.cpu().numpy()
+    close(a[:, :B], a_ref, 1e-4, "a")
+    assert np.all(a[:, B:] == 7.0), "columns >= B were written"
+    close(g, O.grad_val, 1e-4, "grad_val")
+    close(gb, O.grad_bias, 1e-4, "grad_bias")
+    if need_gx:
+        gx = gxd.cpu().numpy()
+        close(gx[:, :B], gx_ref, 1e-4, "grad_x")
+        assert np.all(gx[:, B:] == 7.0)
+    O.update()
+    G.update()
+    r2, c2, val2, vel2, bias2, bvel2 = G.export_csr()
+    assert np.array_equal(r2, O.rowptr) and np.array_equal(c2, O.colidx)
+    close(val2, O.val, 1e-4, "val")
+    close(vel2, O.vel, 1e-4, "vel")
+    close(bias2, O.bias, 1e-4, "bias")
+    close(bvel2, O.bias_vel, 1e-4, "bias_vel")
+    # the update itself is plain fp32 arithmetic: bit-exact when fed the GPU's own gradient
+    O.set_state(rowptr, colidx, val, vel, bias, bias_vel)
+    O.grad_val, O.grad_bias = g.copy(), gb.copy()
+    O.update()
+    assert np.array_equal(val2.view(np.uint32), O.val.view(np.uint32))
+    assert np.array_equal(vel2.view(np.uint32), O.vel.view(np.uint32))
+    assert np.array_equal(bias2.view(np.uint32), O.bias.view(np.uint32))
+    G.close()
+
+
+def test_softmax_cross_entropy(gpu, oracle):
+    import torch
+    rng = np.random.default_rng(3)
+    for C, B in [(2, 128), (10, 96), (10, 1), (7, 300)]:
+        z = (rng.standard_normal((C, B)) * 4).astype(np.float32)
+        y = rng.integers(0, C, size=B).astype(np.int32)
+        ld = B + 8
+        zd = dev(torch, pad_cols(z, ld))
+        dzd = torch.full((C, ld), 7.0, dtype=torch.float32, device="cuda:0")
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+        gpu.softmax_ce(zd, dev(torch, y), B, C, dzd, loss)
+        loss_ref, dz_ref = oracle.softmax_ce(z, y)
+        dz = dzd.cpu().numpy()
+        close(dz[:, :B], dz_ref, 1e-5, "dz")
+        assert np.all(dz[:, B:] == 7.0)
+        assert abs(loss.item() / B - loss_ref) <= 1e-5 * max(1.0, abs(loss_ref))
+
+
+# ------------------------------------------------------------------------------------------ evolve
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("n_in,n_out,nnz,need_gx", [
+    (500, 400, 9000, False), (400, 100, 5000, True), (400, 2, 800, True), (64, 48, 1000, True),
+    (3000, 5000, 37, True), (100000, 70000, 1700000, True)])
+def test_evolve_bit_exact(gpu, oracle, mode, n_in, n_out, nnz, need_gx):
+    G, O = make_pair(gpu, oracle, n_in, n_out, nnz, prune_mode=mode, need_input_grad=need_gx, seed=99)
+    rng = np.random.default_rng(nnz)
+    rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+    # trained-looking weights; a few exact ties and zeros to exercise the tie rule
+    val = (rng.standard_normal(nnz) * 0.1).astype(np.float32)
+    if nnz >= 100:
+        val[rng.integers(0, nnz, size=nnz // 10)] = np.float32(0.03125)
+        val[rng.integers(0, nnz, size=nnz // 20)] = np.float32(-0.03125)
+        val[rng.integers(0, nnz, size=5)] = 0.0
+    vel = (rng.standard_normal(nnz) * 0.01).astype(np.float32)
+    for gen in (1, 2, 3):
+        G.import_csr(rowptr, colidx, val, vel, bias, bias_vel)
+        O.set_state(rowptr, colidx, val, vel, bias, bias_vel)
+        k = O.evolve(0.3, gen)
+        G.evolve(0.3, gen)
+        assert G.nnz == nnz
+        assert_same_topology(G, O)
+        rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+        assert int((vel == 0).sum()) >= k
+    G.close()
+
+
+def test_evolve_all_ties_and_zero_fraction(gpu, oracle):
+    G, O = make_pair(gpu, oracle, 300, 200, 4000, seed=5)
+    rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+    val[:] = np.where(np.arange(4000) % 2 == 0, 0.25, -0.25)
+    G.import_csr(rowptr, colidx, val, vel, bias, bias_vel)
+    O.set_state(rowptr, colidx, val, vel, bias, bias_vel)
+    O.evolve(0.3, 1)
+    G.evolve(0.3, 1)
+    assert_same_topology(G, O)
+    before = G.export_csr()
+    G.evolve(0.0, 2)
+    after = G.export_csr()
+    assert all(np.array_equal(a, b) for a, b in zip(before, after))
+    G.close()
+
+
+# ------------------------------------------------------------------------------------------ whole network
+def run_network(gpu, oracle, w, n_steps, check_first_step=True):
+    import torch
+    X, y = wl.dataset(w, n_steps * w.batch)
+    blocks = wl.to_batch_blocks(X, w.batch)
+    net = gpu.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=w.batch)
+    olayers = [oracle.OracleLayer(s.n_in, s.n_out, s.nnz, s.act_kind, s.act_parity, w.alpha, s.init_limit, w.lr,
+                                  w.momentum, 0.0, w.seed, s.layer_id) for s in w.layers]
+    onet = oracle.OracleMLP(olayers)
+    for G, O in zip(net.layers, olayers):
+        assert_same_topology(G, O)
+    xd = dev(torch, blocks)
+    yd = dev(torch, y)
+    losses = []
+    for k in range(n_steps):
+        B = min(w.batch, X.shape[0] - k * w.batch)
+        losses.append(onet.train_step(blocks[k][:, :B], y[k * w.batch:k * w.batch + B]))
+        net.train_step(xd[k], yd[k * w.batch:k * w.batch + B], B)
+        if k == 0 and check_first_step:
+            for li, (G, O) in enumerate(zip(net.layers, olayers)):
+                close(net.acts[li].cpu().numpy()[:, :B], onet.acts[li + 1], 1e-4, f"act {li}")
+                _, _, val, vel, bias, bias_vel = G.export_csr()
+                close(val, O.val, 1e-4, f"val {li}")
+                close(vel, O.vel, 1e-4, f"vel {li}")
+                close(bias, O.bias, 1e-4, f"bias {li}")
+    gpu_loss = net.loss_sum.item()
+    return net, onet, olayers, losses, gpu_loss
+
+
+def test_madelon_shaped_epoch_and_evolution(gpu, oracle):
+    w = wl.WORKLOADS["set_mlp_madelon"]
+    steps = w.steps_per_epoch
+    net, onet, olayers, losses, gpu_loss = run_network(gpu, oracle, w, steps)
+    assert abs(gpu_loss - sum(losses)) <= 1e-3 * abs(sum(losses))
+    for li, (G, O) in enumerate(zip(net.layers, olayers)):
+        rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+        assert np.array_equal(rowptr, O.rowptr) and np.array_equal(colidx, O.colidx)
+        close(val, O.val, 1e-3, f"epoch val {li}")
+        close(vel, O.vel, 1e-3, f"epoch vel {li}")
+        close(bias, O.bias, 1e-3, f"epoch bias {li}")
+        # evolution as a function of bit-identical inputs: feed the GPU's weights to the oracle
+        O.set_state(rowptr, colidx, val, vel, bias, bias_vel)
+    net.evolve(w.zeta, 1)
+    onet.evolve(w.zeta, 1)
+    for G, O, s in zip(net.layers, olayers, w.layers):
+        assert G.nnz == s.nnz
+        assert_same_topology(G, O)
+    # the evolved network keeps training
+    import torch
+    X, y = wl.dataset(w, w.batch)
+    blocks = wl.to_batch_blocks(X, w.batch)
+    l0 = onet.train_step(blocks[0], y)
+    net.loss_sum.zero_()
+    net.train_step(dev(torch, blocks[0]), dev(torch, y), w.batch)
+    assert abs(net.loss_sum.item() - l0) <= 1e-4 * abs(l0)
+    net.close()
+
+
+@pytest.mark.parametrize("name,steps", [("set_mlp_fmnist", 3), ("set_mlp_cifar", 2)])
+def test_image_shaped_networks_first_steps(gpu, oracle, name, steps):
+    w = wl.WORKLOADS[name]
+    net, onet, olayers, losses, gpu_loss = run_network(gpu, oracle, w, steps)
+    assert abs(gpu_loss - sum(losses)) <= 1e-4 * abs(sum(losses))
+    for li, (G, O) in enumerate(zip(net.layers, olayers)):
+        _, _, val, vel, bias, _ = G.export_csr()
+        close(val, O.val, 3e-4, f"val {li}")
+        close(vel, O.vel, 3e-4, f"vel {li}")
+    net.close()
