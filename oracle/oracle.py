@@ -268,11 +268,18 @@ class OracleMLP:
     def __init__(self, layers: List[OracleLayer]):
         self.layers = layers
         self.acts: List[np.ndarray] = []
+        # optional callable(layer_index, layer, a) -> a, run after each layer's forward.  Tests use
+        # it to look at pre-activations that sit on the kink of eq. (3), where the branch taken is
+        # decided by rounding, and to evaluate the other branch.
+        self.after_forward = None
 
     def forward(self, x: np.ndarray) -> np.ndarray:
         self.acts = [np.ascontiguousarray(x, dtype=np.float32)]
-        for layer in self.layers:
-            self.acts.append(layer.forward(self.acts[-1]))
+        for li, layer in enumerate(self.layers):
+            a = layer.forward(self.acts[-1])
+            if self.after_forward is not None:
+                a = self.after_forward(li, layer, a)
+            self.acts.append(a)
         return self.acts[-1]
 
     def train_step(self, x: np.ndarray, y: np.ndarray) -> float:

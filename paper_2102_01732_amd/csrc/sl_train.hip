@@ -313,20 +313,21 @@ __global__ __launch_bounds__(BLOCK) void update_kernel(long n, float *w, float *
                                                       float mu, float wd, const int *scatter_pos, float *w_csr,
                                                       int nb, float *bias, float *bias_vel, const float *gbias)
 {
+#pragma clang fp contract(off)   // separate roundings: this must equal the plain fp32 evaluation
     const long t = (long)blockIdx.x * BLOCK + threadIdx.x;
     if (t < n) {
         const float wt = w[t];
-        const float gg = __fadd_rn(g[t], __fmul_rn(wd, wt));
-        const float vn = __fsub_rn(__fmul_rn(mu, vel[t]), __fmul_rn(lr, gg));
-        const float wn = __fadd_rn(wt, vn);
+        const float gg = g[t] + wd * wt;
+        const float vn = mu * vel[t] - lr * gg;
+        const float wn = wt + vn;
         vel[t] = vn;
         w[t] = wn;
         if (scatter_pos) w_csr[scatter_pos[t]] = wn;
     } else if (t - n < nb) {
         const long j = t - n;
-        const float vn = __fsub_rn(__fmul_rn(mu, bias_vel[j]), __fmul_rn(lr, gbias[j]));
+        const float vn = mu * bias_vel[j] - lr * gbias[j];
         bias_vel[j] = vn;
-        bias[j] = __fadd_rn(bias[j], vn);
+        bias[j] = bias[j] + vn;
     }
 }
 
