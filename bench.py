@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the truly sparse SET-MLP training hot path on one MI355X.
+
+A "step" is one minibatch through the whole path: forward SpMM + All-ReLU of every layer, softmax
+cross-entropy, backward (transposed SpMM + SDDMM) of every layer, momentum-SGD update; after every
+`steps_per_epoch` steps the SET prune/regrow evolution of every layer runs inside the timed region.
+Inputs are synthetic and already resident in HBM when the clock starts.
+
+Prints ONE JSON line: throughput in samples/s, the HBM roofline of the dominant kernel (measured
+live with HIP events on the launch stream) and the CPU oracle timed on this host for context.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(kernel, spec, B, has_csc):
+    """Compulsory HBM bytes of one launch (every operand once) and the no-reuse gather model (every
+    stored connection fetches its own 4*B-byte operand row)."""
+    nnz, n_in, n_out = spec.nnz, spec.n_in, spec.n_out
+    row = 4 * B
+    if kernel == "forward_spmm":
+        fixed = 8 * nnz + 4 * (n_out + 1) + 4 * n_out + row * n_out + (B // 4) * n_out * (1 if spec.act_kind else 0)
+        return fixed + row * n_in, fixed + row * nnz
+    if kernel == "backward_fused":
+        fixed = 8 * nnz + 4 * (n_in + 1) + 2 * row * n_in + 4 * nnz
+        return fixed + row * n_out, fixed + row * nnz
+    if kernel == "sddmm":
+        fixed = 4 * nnz + 4 * (n_out + 1) + row * n_out + 4 * nnz
+        return fixed + row * n_in, fixed + row * nnz
+    if kernel == "act_grad":
+        b = 2 * row * n_out + (B // 4) * n_out + 4 * n_out
+        return b, b
+    if kernel == "update":
+        b = (28 if has_csc else 20) * nnz + 20 * n_out
+        return b, b
+    return 0, 0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="set_mlp_1m")
+    ap.add_argument("--profile-steps", type=int, default=8)
+    ap.add_argument("--cpu-samples", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2102_01732_amd import binding, workloads as wl
+
+    binding.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    w = wl.WORKLOADS[args.workload]
+    B = w.batch
+    K = args.steps if args.steps is not None else w.steps_per_epoch
+    n_blocks = w.steps_per_epoch
+    n_in = w.dims[0]
+
+    # ---- synthetic data, resident in HBM, feature-major minibatch blocks [n_blocks][n_in][B]
+    if w.n_samples * n_in > 2 ** 28:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed)
+        blocks = torch.empty((n_blocks, n_in, B), dtype=torch.float32, device=dev)
+        h = torch.randn(n_in, generator=gen, device=dev)
+        labels = torch.empty((n_blocks, B), dtype=torch.int32, device=dev)
+        for k in range(n_blocks):
+            blocks[k].normal_(generator=gen)
+            labels[k] = (h @ blocks[k] > 0).to(torch.int32)
+        sizes = [B] * n_blocks
+        data_note = "synthetic N(0,1) features generated on the device, labels from a seeded random hyperplane"
+    else:
+        X, y = wl.dataset(w)
+        blocks = torch.from_numpy(wl.to_batch_blocks(X, B)).to(dev)
+        ypad = np.zeros(n_blocks * B, np.int32)
+        ypad[: y.size] = y
+        labels = torch.from_numpy(ypad.reshape(n_blocks, B)).to(dev)
+        sizes = [min(B, w.n_samples - k * B) for k in range(n_blocks)]
+        data_note = f"synthetic {w.feature_law} features, labels from a seeded random linear teacher"
+
+    net = binding.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=B)
+    generation = [0]
+
+    def step(i):
+        k = i % n_blocks
+        net.train_step(blocks[k], labels[k], sizes[k])
+        if (i + 1) % n_blocks == 0:
+            generation[0] += 1
+            net.evolve(w.zeta, generation[0])
+
+    for i in range(args.warmup):
+        net.train_step(blocks[i % n_blocks], labels[i % n_blocks], sizes[i % n_blocks])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    samples = 0
+    for i in range(K):
+        step(i)
+        samples += sizes[i % n_blocks]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    value = samples / elapsed
+
+    # ---- evolution alone (one generation, all layers)
+    torch.cuda.synchronize()
+    te0 = time.perf_counter()
+    generation[0] += 1
+    net.evolve(w.zeta, generation[0])
+    torch.cuda.synchronize()
+    evolve_ms = (time.perf_counter() - te0) * 1e3
+
+    # ---- per-kernel durations with HIP events on the launch stream
+    for layer in net.layers:
+        layer.profile_begin()
+    P = max(1, args.profile_steps)
+    for i in range(P):
+        net.train_step(blocks[i % n_blocks], labels[i % n_blocks], sizes[i % n_blocks])
+    torch.cuda.synchronize()
+    kernels = []
+    for li, (layer, spec) in enumerate(zip(net.layers, w.layers)):
+        for name, (n, ms) in layer.profile_end().items():
+            comp, gather = algorithmic_bytes(name, spec, B, li > 0)
+            avg_ms = ms / n
+            kernels.append(dict(layer=li, kernel=name, launches_per_step=n / P, avg_ms=avg_ms,
+                                algorithmic_bytes=comp, gather_model_bytes=gather,
+                                achieved_gbs=comp / avg_ms / 1e6 if comp else None,
+                                gather_model_gbs=gather / avg_ms / 1e6 if gather else None))
+    kernels.sort(key=lambda r: -r["avg_ms"] * r["launches_per_step"])
+    dom = kernels[0]
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tfile):
+        try:
+            t = json.load(open(tfile))
+            traffic = t.get(args.workload, {}).get(f"{dom['kernel']}:L{dom['layer']}")
+        except Exception:
+            traffic = None
+    roofline = dict(bound="hbm", kernel=dom["kernel"], layer=dom["layer"], achieved=dom["achieved_gbs"],
+                    peak=HBM_PEAK_GBS, unit="GB/s", frac=dom["achieved_gbs"] / HBM_PEAK_GBS, traffic=traffic,
+                    avg_ms=dom["avg_ms"], algorithmic_bytes=dom["algorithmic_bytes"],
+                    gather_model_gbs=dom["gather_model_gbs"],
+                    gather_model_frac=dom["gather_model_gbs"] / HBM_PEAK_GBS)
+
+    # ---- CPU oracle on this host, bounded sample (reported baseline, not the target)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        ns = max(1, min(args.cpu_samples, sizes[0]))
+        xs = blocks[0][:, :ns].contiguous().cpu().numpy()
+        ys = labels[0][:ns].cpu().numpy()
+        olayers = [orc.OracleLayer(s.n_in, s.n_out, s.nnz, s.act_kind, s.act_parity, w.alpha, s.init_limit, w.lr,
+                                   w.momentum, 0.0, w.seed, s.layer_id) for s in w.layers]
+        onet = orc.OracleMLP(olayers)
+        c0 = time.perf_counter()
+        onet.train_step(xs, ys)
+        c1 = time.perf_counter()
+        cpu = dict(value=ns / (c1 - c0), unit="samples/s", cores=1, kind="oracle",
+                   sample=f"one training step (forward, loss, backward, update) on the first {ns} samples of "
+                          f"minibatch 0 at the full layer shapes; {c1 - c0:.1f} s; evolution not included")
+
+    out = dict(metric="sparse-MLP train samples/s", value=value, unit="samples/s", n_gpus=1, steps=K,
+               warmup=args.warmup, ms_per_step=elapsed / K * 1e3, higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype="f32", data=data_note,
+               config=dict(workload=args.workload, dims=list(w.dims), epsilon=w.epsilon, batch=B,
+                           nnz=[s.nnz for s in w.layers], alpha=w.alpha, zeta=w.zeta,
+                           evolutions_in_timed_region=K // n_blocks, parallelism="single GPU"),
+               roofline=roofline, cpu_baseline=cpu, evolve_ms_all_layers=evolve_ms, kernels=kernels[:12])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -128,6 +128,15 @@ int sparse_layer_export_grad(sl_layer *layer, float *grad_val, float *grad_bias)
 int sparse_layer_set_lr(sl_layer *layer, float lr);
 const char *sparse_layer_last_error(const sl_layer *layer);
 
+/* Per-kernel timing (tracing aid, off by default).  Between profile_begin and profile_end every
+ * kernel the layer launches is bracketed by HIP events on the caller's stream.  profile_end waits
+ * for them and returns, per kernel id < n_ids, the number of launches and their summed duration
+ * in milliseconds (host arrays).  Ids: see sparse_kernel_name (0 forward SpMM, 1 forward fix-up,
+ * 2 activation gradient, 3 fused backward, 4 SDDMM, 5 backward fix-up, 6 update). */
+int sparse_layer_profile_begin(sl_layer *layer);
+int sparse_layer_profile_end(sl_layer *layer, int32_t *launches, float *total_ms, int32_t n_ids);
+const char *sparse_kernel_name(int32_t id);
+
 #ifdef __cplusplus
 }
 #endif

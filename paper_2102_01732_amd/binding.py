@@ -24,8 +24,10 @@ EXPORTS = [
     "sparse_layer_query_sizes", "sparse_layer_init", "sparse_layer_forward", "sparse_layer_backward",
     "sparse_layer_update", "sparse_layer_evolve", "sparse_layer_destroy", "sparse_loss_softmax_ce",
     "sparse_layer_nnz", "sparse_layer_export_csr", "sparse_layer_import_csr", "sparse_layer_export_grad",
-    "sparse_layer_set_lr", "sparse_layer_last_error",
+    "sparse_layer_set_lr", "sparse_layer_last_error", "sparse_layer_profile_begin", "sparse_layer_profile_end",
+    "sparse_kernel_name",
 ]
+N_KERNEL_IDS = 7
 
 
 class SlConfig(C.Structure):
@@ -66,8 +68,12 @@ def lib():
         L.sparse_layer_set_lr.argtypes = [vp, C.c_float]
         L.sparse_layer_last_error.argtypes = [vp]
         L.sparse_layer_last_error.restype = C.c_char_p
+        L.sparse_layer_profile_begin.argtypes = [vp]
+        L.sparse_layer_profile_end.argtypes = [vp, vp, vp, i32]
+        L.sparse_kernel_name.argtypes = [i32]
+        L.sparse_kernel_name.restype = C.c_char_p
         for name in EXPORTS:
-            if name != "sparse_layer_last_error":
+            if name not in ("sparse_layer_last_error", "sparse_kernel_name"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -170,6 +176,16 @@ class SparseLayer:
         self._check(lib().sparse_layer_export_grad(self.handle, g.ctypes.data, gb.ctypes.data),
                     "sparse_layer_export_grad")
         return g[: self.nnz], gb
+
+    def profile_begin(self):
+        self._check(lib().sparse_layer_profile_begin(self.handle), "sparse_layer_profile_begin")
+
+    def profile_end(self):
+        """{kernel name: (launches, total ms)} since profile_begin."""
+        n = (C.c_int32 * N_KERNEL_IDS)()
+        ms = (C.c_float * N_KERNEL_IDS)()
+        self._check(lib().sparse_layer_profile_end(self.handle, n, ms, N_KERNEL_IDS), "sparse_layer_profile_end")
+        return {lib().sparse_kernel_name(i).decode(): (n[i], ms[i]) for i in range(N_KERNEL_IDS) if n[i]}
 
     def close(self):
         if self.handle:

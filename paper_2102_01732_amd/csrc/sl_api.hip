@@ -313,9 +313,54 @@ int sparse_layer_evolve(sl_layer *L, double zeta, uint64_t generation, void *hip
     return SL_OK;
 }
 
+static void drop_profile(sl_layer *L)
+{
+    for (auto &r : L->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    L->prof.clear();
+}
+
+int sparse_layer_profile_begin(sl_layer *L)
+{
+    if (!L) return SL_EINVAL;
+    drop_profile(L);
+    L->prof_on = true;
+    return SL_OK;
+}
+
+int sparse_layer_profile_end(sl_layer *L, int32_t *launches, float *total_ms, int32_t n_ids)
+{
+    if (!L) return SL_EINVAL;
+    L->prof_on = false;
+    for (int i = 0; i < n_ids; ++i) {
+        if (launches) launches[i] = 0;
+        if (total_ms) total_ms[i] = 0.f;
+    }
+    int rc = SL_OK;
+    for (auto &r : L->prof) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(r.stop);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
+        if (e != hipSuccess) { rc = set_err(L, SL_EHIP, "profile: %s", hipGetErrorString(e)); break; }
+        if (r.id < n_ids) {
+            if (launches) launches[r.id] += 1;
+            if (total_ms) total_ms[r.id] += ms;
+        }
+    }
+    drop_profile(L);
+    return rc;
+}
+
+const char *sparse_kernel_name(int32_t id)
+{
+    static const char *names[K_COUNT] = {"forward_spmm", "forward_fixup", "act_grad", "backward_fused",
+                                         "sddmm", "backward_fixup", "update"};
+    return (id >= 0 && id < K_COUNT) ? names[id] : "";
+}
+
 int sparse_layer_destroy(sl_layer *L)
 {
     if (!L) return SL_EINVAL;
+    drop_profile(L);
     delete L;
     return SL_OK;
 }

@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "sparse_set.h"
 
 namespace sl {
@@ -78,6 +80,10 @@ struct sl_layer {
     float *dz = nullptr;
     sl::SelState *sel = nullptr;
     sl::SegMat fwd, bwd;
+    // optional per-kernel timing with HIP events on the caller's stream (off by default)
+    struct ProfRec { int id; hipEvent_t start, stop; };
+    bool prof_on = false;
+    std::vector<ProfRec> prof;
     int phase = 0;     // 0 idle, 1 forward done, 2 backward done
     int last_B = 0;
     hipStream_t last_stream = nullptr;
@@ -92,6 +98,22 @@ int set_err(sl_layer *L, int code, const char *fmt, ...);
         hipError_t e__ = (expr);                                                              \
         if (e__ != hipSuccess) return sl::set_err((L), SL_EHIP, "%s: %s", #expr, hipGetErrorString(e__)); \
     } while (0)
+
+// kernel ids reported by the profiling calls
+enum KernelId { K_FWD = 0, K_FWD_FIX, K_ACTGRAD, K_BWD_FUSED, K_SDDMM, K_BWD_FIX, K_UPDATE, K_COUNT };
+struct ProfScope {
+    sl_layer *L; hipStream_t s; hipEvent_t stop = nullptr;
+    ProfScope(sl_layer *L_, int id, hipStream_t s_) : L(L_), s(s_)
+    {
+        if (!L->prof_on || L->prof.size() >= 65536) return;
+        hipEvent_t a = nullptr;
+        if (hipEventCreate(&a) != hipSuccess) return;
+        if (hipEventCreate(&stop) != hipSuccess) { (void)hipEventDestroy(a); stop = nullptr; return; }
+        (void)hipEventRecord(a, s);
+        L->prof.push_back({id, a, stop});
+    }
+    ~ProfScope() { if (stop) (void)hipEventRecord(stop, s); }
+};
 
 // host-side planning (no GPU needed)
 int64_t config_nnz(const sl_config &c);

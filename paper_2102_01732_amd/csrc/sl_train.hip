@@ -392,6 +392,7 @@ int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, in
         dispatch_g(G, [&](auto g) {
             constexpr int GG = decltype(g)::value;
             dim3 grid((unsigned)((m.nv + BLOCK / GG - 1) / (BLOCK / GG)), (unsigned)tiles);
+            ProfScope ps(L, K_FWD, s);
             hipLaunchKernelGGL(fwd_kernel<GG>, grid, dim3(BLOCK), 0, s, f);
         });
     } else {
@@ -402,8 +403,12 @@ int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, in
         dispatch_g(G, [&](auto g) {
             constexpr int GG = decltype(g)::value;
             dim3 grid((unsigned)((m.nv + BLOCK / GG - 1) / (BLOCK / GG)), (unsigned)tiles);
-            hipLaunchKernelGGL(fwd_kernel<GG>, grid, dim3(BLOCK), 0, s, pa);
+            {
+                ProfScope ps(L, K_FWD, s);
+                hipLaunchKernelGGL(fwd_kernel<GG>, grid, dim3(BLOCK), 0, s, pa);
+            }
             dim3 grid2((unsigned)((m.n_rows + BLOCK / GG - 1) / (BLOCK / GG)), (unsigned)tiles);
+            ProfScope ps(L, K_FWD_FIX, s);
             hipLaunchKernelGGL(fix_kernel<GG>, grid2, dim3(BLOCK), 0, s, fx);
         });
     }
@@ -420,6 +425,7 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
     dispatch_g(G, [&](auto g) {
         constexpr int GG = decltype(g)::value;
         dim3 grid((unsigned)((n_out + BLOCK / GG - 1) / (BLOCK / GG)));
+        ProfScope ps(L, K_ACTGRAD, s);
         hipLaunchKernelGGL(actgrad_kernel<GG>, grid, dim3(BLOCK), 0, s, ga, (long)ldg, L->mask, (long)L->ldm, L->dz,
                            (long)L->ldz, L->grad_bias, n_out, B, L->cfg.act_kind, slope);
     });
@@ -434,8 +440,11 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
         dispatch_g(G, [&](auto g) {
             constexpr int GG = decltype(g)::value;
             dim3 grid((unsigned)((m.nv + BLOCK / GG - 1) / (BLOCK / GG)));
-            if (ragged) hipLaunchKernelGGL((bwd_kernel<GG, true, true>), grid, dim3(BLOCK), 0, s, b);
-            else hipLaunchKernelGGL((bwd_kernel<GG, true, false>), grid, dim3(BLOCK), 0, s, b);
+            {
+                ProfScope ps(L, K_BWD_FUSED, s);
+                if (ragged) hipLaunchKernelGGL((bwd_kernel<GG, true, true>), grid, dim3(BLOCK), 0, s, b);
+                else hipLaunchKernelGGL((bwd_kernel<GG, true, false>), grid, dim3(BLOCK), 0, s, b);
+            }
             if (m.split) {
                 FixArgs fx;
                 fx.rvptr = m.rvptr; fx.n_rows = m.n_rows; fx.part = b.out; fx.ldp = L->ldz;
@@ -444,6 +453,7 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
                 fx.f.mask = nullptr; fx.f.ldm = 0; fx.f.B = B; fx.f.act_kind = 0; fx.f.slope = 0.f; fx.f.partial = 0;
                 const int tiles = (B + 4 * GG - 1) / (4 * GG);
                 dim3 grid2((unsigned)((m.n_rows + BLOCK / GG - 1) / (BLOCK / GG)), (unsigned)tiles);
+                ProfScope ps(L, K_BWD_FIX, s);
                 hipLaunchKernelGGL(fix_kernel<GG>, grid2, dim3(BLOCK), 0, s, fx);
             }
         });
@@ -454,6 +464,7 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
         dispatch_g(G, [&](auto g) {
             constexpr int GG = decltype(g)::value;
             dim3 grid((unsigned)((m.nv + BLOCK / GG - 1) / (BLOCK / GG)));
+            ProfScope ps(L, K_SDDMM, s);
             if (ragged) hipLaunchKernelGGL((bwd_kernel<GG, false, true>), grid, dim3(BLOCK), 0, s, b);
             else hipLaunchKernelGGL((bwd_kernel<GG, false, false>), grid, dim3(BLOCK), 0, s, b);
         });
@@ -468,6 +479,7 @@ int launch_update(sl_layer *L, hipStream_t s)
     const int nb = (int)L->cfg.n_out;
     const long total = n + nb;
     dim3 grid((unsigned)((total + BLOCK - 1) / BLOCK));
+    ProfScope ps(L, K_UPDATE, s);
     if (L->has_csc)
         hipLaunchKernelGGL(update_kernel, grid, dim3(BLOCK), 0, s, n, L->valT, L->velT, L->grad, L->cfg.lr,
                            L->cfg.momentum, L->cfg.weight_decay, L->csr_pos, L->val, nb, L->bias, L->bias_vel,
