@@ -1,0 +1,97 @@
+"""Full-size parity: the one-million-neuron workload in exactly the launch configuration that
+bench.py times (B = 128, all four layers on one GPU), against digests and sampled values that
+tests/golden/make_1m_golden.py computed with the CPU oracle alone.  Topology, indices and fresh
+weights are compared bit for bit over ALL entries (sha256); fp32 tensors on sampled neurons and
+every 8192nd connection, within 1e-4 of the tensor's largest oracle magnitude."""
+import hashlib
+import json
+import os
+
+import numpy as np
+import pytest
+
+from paper_2102_01732_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "set_mlp_1m_step.json")
+
+
+def digest(a):
+    return hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()
+
+
+def near(got, ref, absmax, tol, what):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, what
+    err = np.abs(got - ref).max()
+    assert np.all(np.isfinite(got)) and err <= tol * absmax, f"{what}: max abs err {err:.3e} > {tol} * {absmax:.3e}"
+
+
+@pytest.fixture(scope="module")
+def setup():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2102_01732_amd import binding
+    binding.lib()
+    return binding, json.load(open(GOLDEN)), wl.WORKLOADS["set_mlp_1m"]
+
+
+def make_net(binding, w):
+    return binding.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=w.batch)
+
+
+def test_one_million_neuron_init_and_evolution_bit_exact(setup):
+    binding, golden, w = setup
+    net = make_net(binding, w)
+    for li, (G, g) in enumerate(zip(net.layers, golden["layers"])):
+        rowptr, colidx, val, vel, bias, _ = G.export_csr()
+        assert G.nnz == w.layers[li].nnz
+        assert digest(rowptr) == g["init"]["rowptr"], f"layer {li} rowptr"
+        assert digest(colidx) == g["init"]["colidx"], f"layer {li} colidx"
+        assert digest(val) == g["init"]["val"], f"layer {li} val"
+        assert not vel.any() and not bias.any()
+    net.evolve(w.zeta, 1)
+    for li, (G, g) in enumerate(zip(net.layers, golden["layers"])):
+        rowptr, colidx, val, vel, _, _ = G.export_csr()
+        assert G.nnz == w.layers[li].nnz
+        assert int((vel == 0).sum()) == w.layers[li].nnz          # zero velocities everywhere (fresh network)
+        assert digest(rowptr) == g["evolved"]["rowptr"], f"layer {li} rowptr after evolution"
+        assert digest(colidx) == g["evolved"]["colidx"], f"layer {li} colidx after evolution"
+        assert digest(val) == g["evolved"]["val"], f"layer {li} val after evolution"
+        assert digest(vel) == g["evolved"]["vel"]
+    net.close()
+
+
+def test_one_million_neuron_training_step(setup):
+    import torch
+    binding, golden, w = setup
+    B = w.batch
+    X, y = wl.dataset(w, B)
+    x0 = torch.from_numpy(wl.to_batch_blocks(X, B)[0]).cuda()
+    yd = torch.from_numpy(y).cuda()
+    net = make_net(binding, w)
+    zL = net.forward(x0, B)
+    binding.softmax_ce(zL, yd, B, net.n_classes, net.grads[-1], net.loss_sum)
+    for li in range(len(net.layers) - 1, -1, -1):
+        xin = x0 if li == 0 else net.acts[li - 1]
+        net.layers[li].backward(xin, net.grads[li], B, net.grads[li - 1] if li > 0 else None)
+    stride = golden["val_stride"]
+    grads = [G.export_grad() for G in net.layers]
+    for G in net.layers:
+        G.update()
+    torch.cuda.synchronize()
+    loss = net.loss_sum.item() / B
+    assert abs(loss - golden["loss_mean"]) <= 1e-4 * abs(golden["loss_mean"])
+    for li, (G, g) in enumerate(zip(net.layers, golden["layers"])):
+        s = g["step"]
+        rows = torch.tensor(s["rows"], device="cuda")
+        act = net.acts[li][rows][:, :B].cpu().numpy()
+        near(act, s["act"], s["act_absmax"], 1e-4, f"layer {li} activations")
+        idx = np.arange(0, G.nnz, stride)
+        near(grads[li][0][idx], s["grad_val"], s["grad_val_absmax"], 1e-4, f"layer {li} weight gradient")
+        _, _, val, vel, bias, _ = G.export_csr()
+        near(val[idx], s["val"], np.abs(s["val"]).max(), 1e-4, f"layer {li} weights")
+        near(vel[idx], s["vel"], s["vel_absmax"], 1e-4, f"layer {li} velocities")
+        near(bias[np.asarray(s["rows"])], s["bias"], s["bias_absmax"], 1e-4, f"layer {li} biases")
+    net.close()
