@@ -92,10 +92,20 @@ int sparse_layer_forward(sl_layer *layer, const float *x_dev, int64_t ldx, int32
  *   grad_val[p]  = sum_b dz[j][b] * x[i][b]   for every stored connection p = (j,i) only
  *   grad_x[i][b] = sum_{j:(j,i) stored} Wt[j,i] * dz[j][b]   (weights before the update)
  * grad_a_dev [n_out][ldg]; x_dev is the x passed to forward; grad_x_dev [n_in][ldgx] must be
- * non-NULL iff the layer was created with SL_FLAG_NEED_INPUT_GRAD.  The 1/B of the minibatch
+ * non-NULL iff the layer was created with SL_FLAG_NEED_INPUT_GRAD (but see
+ * sparse_layer_link_producer, which allows NULL for both gradients inside a chain).  The 1/B of the minibatch
  * mean (Algorithm 1's worker gradient) is carried by grad_a of the output layer.  Asynchronous. */
 int sparse_layer_backward(sl_layer *layer, const float *x_dev, int64_t ldx, const float *grad_a_dev,
                           int64_t ldg, int32_t B, float *grad_x_dev, int64_t ldgx, void *hip_stream);
+
+/* Chaining (optional).  Declares that `layer`'s input x is the activation output of `producer`
+ * (same stream, same minibatch).  After that, sparse_layer_backward(layer, ...) may be called with
+ * grad_x_dev == NULL: the input gradient is then multiplied by the producer's f' (eq. 3, from its
+ * saved sign mask) and stored as the producer's dz, with its bias gradient, inside the same kernel,
+ * and the producer's next sparse_layer_backward may be called with grad_a_dev == NULL.  This removes
+ * one read and one write of the [n][B] gradient per hidden layer.  producer == NULL unlinks.
+ * The producer must outlive the link. */
+int sparse_layer_link_producer(sl_layer *layer, sl_layer *producer);
 
 /* Momentum SGD over the stored connections and the biases, eq. (1) in velocity form:
  * vel <- mu*vel - eta*(grad + weight_decay*w);  w <- w + vel.  Must follow backward.  Asynchronous. */

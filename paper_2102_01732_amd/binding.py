@@ -25,7 +25,7 @@ EXPORTS = [
     "sparse_layer_update", "sparse_layer_evolve", "sparse_layer_destroy", "sparse_loss_softmax_ce",
     "sparse_layer_nnz", "sparse_layer_export_csr", "sparse_layer_import_csr", "sparse_layer_export_grad",
     "sparse_layer_set_lr", "sparse_layer_last_error", "sparse_layer_profile_begin", "sparse_layer_profile_end",
-    "sparse_kernel_name",
+    "sparse_kernel_name", "sparse_layer_link_producer",
 ]
 N_KERNEL_IDS = 7
 
@@ -68,6 +68,7 @@ def lib():
         L.sparse_layer_set_lr.argtypes = [vp, C.c_float]
         L.sparse_layer_last_error.argtypes = [vp]
         L.sparse_layer_last_error.restype = C.c_char_p
+        L.sparse_layer_link_producer.argtypes = [vp, vp]
         L.sparse_layer_profile_begin.argtypes = [vp]
         L.sparse_layer_profile_end.argtypes = [vp, vp, vp, i32]
         L.sparse_kernel_name.argtypes = [i32]
@@ -133,9 +134,14 @@ class SparseLayer:
         self._check(lib().sparse_layer_forward(self.handle, x.data_ptr(), x.stride(0), B, a.data_ptr(), a.stride(0),
                                                _stream()), "sparse_layer_forward")
 
-    def backward(self, x: torch.Tensor, grad_a: torch.Tensor, B: int, grad_x: Optional[torch.Tensor]):
-        self._check(lib().sparse_layer_backward(self.handle, x.data_ptr(), x.stride(0), grad_a.data_ptr(),
-                                                grad_a.stride(0), B, _ptr(grad_x),
+    def link_producer(self, producer: Optional["SparseLayer"]):
+        self._check(lib().sparse_layer_link_producer(self.handle, producer.handle if producer else None),
+                    "sparse_layer_link_producer")
+        self._producer = producer      # keeps the producer alive as long as the link
+
+    def backward(self, x: torch.Tensor, grad_a: Optional[torch.Tensor], B: int, grad_x: Optional[torch.Tensor]):
+        self._check(lib().sparse_layer_backward(self.handle, x.data_ptr(), x.stride(0), _ptr(grad_a),
+                                                grad_a.stride(0) if grad_a is not None else 0, B, _ptr(grad_x),
                                                 grad_x.stride(0) if grad_x is not None else 0, _stream()),
                     "sparse_layer_backward")
 
@@ -225,7 +231,11 @@ class SparseMLP:
         self.scratch = torch.empty(scratch_bytes + 256, dtype=torch.uint8, device=self.device)
         self.layers: List[SparseLayer] = [SparseLayer(c, device, self.scratch) for c in cfgs]
         self.acts = [torch.zeros((s.n_out, self.ld), dtype=torch.float32, device=self.device) for s in layer_specs]
-        self.grads = [torch.zeros((s.n_out, self.ld), dtype=torch.float32, device=self.device) for s in layer_specs]
+        # Layers are chained: each backward hands dz to the layer below inside its own kernel, so only
+        # the output layer needs a gradient buffer.
+        for li in range(1, len(self.layers)):
+            self.layers[li].link_producer(self.layers[li - 1])
+        self.grad_out = torch.zeros((layer_specs[-1].n_out, self.ld), dtype=torch.float32, device=self.device)
         self.loss_sum = torch.zeros(1, dtype=torch.float32, device=self.device)
         self.n_classes = layer_specs[-1].n_out
 
@@ -236,13 +246,18 @@ class SparseMLP:
             cur = a
         return cur
 
+    def backward(self, x: torch.Tensor, B: int):
+        """Backward through all layers; self.grad_out must hold dLoss/dz of the output layer."""
+        last = len(self.layers) - 1
+        for li in range(last, -1, -1):
+            xin = x if li == 0 else self.acts[li - 1]
+            self.layers[li].backward(xin, self.grad_out if li == last else None, B, None)
+
     def train_step(self, x: torch.Tensor, y: torch.Tensor, B: int):
         """x [n_in][ld>=B] feature-major, y int32 [B]."""
         zL = self.forward(x, B)
-        softmax_ce(zL, y, B, self.n_classes, self.grads[-1], self.loss_sum)
-        for li in range(len(self.layers) - 1, -1, -1):
-            xin = x if li == 0 else self.acts[li - 1]
-            self.layers[li].backward(xin, self.grads[li], B, self.grads[li - 1] if li > 0 else None)
+        softmax_ce(zL, y, B, self.n_classes, self.grad_out, self.loss_sum)
+        self.backward(x, B)
         for layer in self.layers:
             layer.update()
 

@@ -262,6 +262,23 @@ int sparse_layer_forward(sl_layer *L, const float *x_dev, int64_t ldx, int32_t B
     if (rc) return rc;
     L->phase = 1;
     L->last_B = B;
+    L->dz_ready = 0;
+    return SL_OK;
+}
+
+int sparse_layer_link_producer(sl_layer *L, sl_layer *producer)
+{
+    if (!L) return SL_EINVAL;
+    if (!producer) { L->producer = nullptr; return SL_OK; }
+    if (producer == L) return set_err(L, SL_EINVAL, "a layer cannot be its own producer");
+    if (!L->has_csc) return set_err(L, SL_EINVAL, "link: the layer was created without SL_FLAG_NEED_INPUT_GRAD");
+    if (producer->cfg.n_out != L->cfg.n_in)
+        return set_err(L, SL_EINVAL, "link: producer has %lld outputs, layer has %lld inputs",
+                       (long long)producer->cfg.n_out, (long long)L->cfg.n_in);
+    if (producer->cfg.max_batch < L->cfg.max_batch)
+        return set_err(L, SL_EINVAL, "link: producer max_batch %d < layer max_batch %d", producer->cfg.max_batch,
+                       L->cfg.max_batch);
+    L->producer = producer;
     return SL_OK;
 }
 
@@ -273,11 +290,20 @@ int sparse_layer_backward(sl_layer *L, const float *x_dev, int64_t ldx, const fl
     if (B != L->last_B) return set_err(L, SL_ESTATE, "backward with B = %d after forward with B = %d", B, L->last_B);
     int rc = check_dense(L, x_dev, ldx, B, "x");
     if (rc) return rc;
-    rc = check_dense(L, grad_a_dev, ldg, B, "grad_a");
-    if (rc) return rc;
-    if (L->has_csc) {
-        rc = check_dense(L, grad_x_dev, ldgx, B, "grad_x");
+    if (grad_a_dev || L->dz_ready != B) {
+        L->dz_ready = 0;   // an explicit grad_a overrides anything a consumer handed over
+        rc = check_dense(L, grad_a_dev, ldg, B, "grad_a");
         if (rc) return rc;
+    }
+    if (L->has_csc) {
+        if (grad_x_dev) {
+            rc = check_dense(L, grad_x_dev, ldgx, B, "grad_x");
+            if (rc) return rc;
+        } else if (!L->producer) {
+            return set_err(L, SL_EINVAL, "grad_x is null and no producer layer is linked");
+        } else if (L->producer->phase < 1 || L->producer->last_B != B) {
+            return set_err(L, SL_ESTATE, "linked producer has not run forward with B = %d", B);
+        }
     } else if (grad_x_dev) {
         return set_err(L, SL_EINVAL, "grad_x given but the layer was created without SL_FLAG_NEED_INPUT_GRAD");
     }

@@ -84,6 +84,12 @@ struct sl_layer {
     struct ProfRec { int id; hipEvent_t start, stop; };
     bool prof_on = false;
     std::vector<ProfRec> prof;
+    // Chaining: `producer` is the layer whose activation output is this layer's x.  When this layer's
+    // backward is called without a grad_x buffer it writes the producer's dz (and bias gradient)
+    // directly and sets the producer's dz_ready to the batch size; the producer's backward then
+    // skips its own activation-derivative pass.
+    sl_layer *producer = nullptr;
+    int dz_ready = 0;
     int phase = 0;     // 0 idle, 1 forward done, 2 backward done
     int last_B = 0;
     hipStream_t last_stream = nullptr;

@@ -7,20 +7,23 @@
 // (G = 8/16/32/64 for B <= 32/64/128/256) owns one virtual row: each lane holds four batch
 // columns as a float4, so a gather of one operand row is a single fully coalesced
 // global_load_dwordx4 across the group, and 64/G rows are in flight per wavefront.  Entries are
-// processed U at a time so that U independent row gathers are outstanding per group; the work is
-// HBM-bound (0.5 flop/byte), so there is no MFMA here.
+// processed U at a time (U = 2/4/8 by mean row length) so that U independent row gathers are
+// outstanding per group; the work is HBM-bound (0.5 flop/byte), so there is no MFMA here.
 #include <stdarg.h>
 #include <stdio.h>
+
+#include <type_traits>
 
 #include "sl_internal.h"
 
 namespace sl {
 
 static constexpr int BLOCK = 256;
-static constexpr int UNROLL = 8;
+static constexpr int FIX_BLOCK = 1024;
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 __device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+__device__ __forceinline__ float4 zero4() { return make_float4(0.f, 0.f, 0.f, 0.f); }
 
 // zero the components of v whose column c+k is >= B (ragged batch sizes only)
 __device__ __forceinline__ float4 clip4(float4 v, int c, int B)
@@ -43,7 +46,73 @@ __device__ __forceinline__ void store_row4(float *row, int c, int B, float4 v)
 }
 
 // ------------------------------------------------------------------------------------------------
-// Forward: z = Wt x + b, a = f_l(z) (eq. 3).  One group per virtual row.
+// What happens to a finished row of accumulators.
+//   EPI_FWD   : + bias, All-ReLU (eq. 3), sign mask of z saved for backward      -> a
+//   EPI_PLAIN : stored as is                                                     -> grad_x
+//   EPI_DZ    : the row is dLoss/da of a neuron of the layer that owns `mask_r`; it is multiplied
+//               by that layer's f' (from its saved sign mask) and stored as its dz, and the row sum
+//               is its bias gradient.  Used by the activation-derivative kernel, and by a consumer
+//               layer's backward to hand the input gradient to its producer without a separate
+//               elementwise pass.
+// ------------------------------------------------------------------------------------------------
+enum { EPI_FWD = 0, EPI_PLAIN = 1, EPI_DZ = 2 };
+struct Epi {
+    int mode;
+    float *out;
+    long ldo;
+    const float *bias;
+    uint8_t *mask_w;
+    const uint8_t *mask_r;
+    long ldm;
+    float *gb;
+    int act_kind;
+    float slope;   // -alpha (even layer) or +alpha (odd layer)
+    int B;
+};
+
+// Every lane of the group must call this (EPI_DZ reduces across the group).
+template <int G>
+__device__ __forceinline__ void finish(const Epi &e, long row, int c, bool active, float4 acc, int lane, int tile)
+{
+    if (e.mode == EPI_FWD) {
+        if (!active) return;
+        const float b = e.bias ? e.bias[row] : 0.f;
+        float4 z = make_float4(acc.x + b, acc.y + b, acc.z + b, acc.w + b);
+        float4 r = z;
+        if (e.act_kind != 0) {
+            const unsigned nib = (z.x > 0.f ? 1u : 0u) | (z.y > 0.f ? 2u : 0u) | (z.z > 0.f ? 4u : 0u) | (z.w > 0.f ? 8u : 0u);
+            e.mask_w[row * e.ldm + (c >> 2)] = (uint8_t)nib;
+            r.x = z.x > 0.f ? z.x : e.slope * z.x;
+            r.y = z.y > 0.f ? z.y : e.slope * z.y;
+            r.z = z.z > 0.f ? z.z : e.slope * z.z;
+            r.w = z.w > 0.f ? z.w : e.slope * z.w;
+        }
+        store_row4(e.out + row * e.ldo, c, e.B, r);
+    } else if (e.mode == EPI_PLAIN) {
+        if (active) store_row4(e.out + row * e.ldo, c, e.B, acc);
+    } else {
+        float4 d = zero4();
+        if (active) {
+            d = acc;
+            if (e.act_kind != 0) {
+                const unsigned nib = e.mask_r[row * e.ldm + (c >> 2)];
+                d.x = d.x * ((nib & 1u) ? 1.f : e.slope);
+                d.y = d.y * ((nib & 2u) ? 1.f : e.slope);
+                d.z = d.z * ((nib & 4u) ? 1.f : e.slope);
+                d.w = d.w * ((nib & 8u) ? 1.f : e.slope);
+            }
+            if (c + 3 >= e.B) d = clip4(d, c, e.B);
+            st4(e.out + row * e.ldo + c, d);   // dz is library-owned: ld >= roundup4(B), zeros past B
+        }
+        float s = (d.x + d.y) + (d.z + d.w);
+#pragma unroll
+        for (int m = G / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m, G);
+        if (lane == 0) e.gb[row] = tile == 0 ? s : e.gb[row] + s;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Forward: z = Wt x + b, a = f_l(z) (eq. 3).  One group per virtual row, batch tiles in grid.y.
 // ------------------------------------------------------------------------------------------------
 struct FwdArgs {
     const int *vptr;
@@ -53,42 +122,21 @@ struct FwdArgs {
     const float *w;
     const float *x;
     long ldx;
-    const float *bias;
-    float *out;      // a [n_out][ldo], or partial sums [nv][ldo] when partial != 0
-    long ldo;
-    uint8_t *mask;   // [n_out][ldm] one byte per float4: bit k set <=> z[4q+k] > 0
-    long ldm;
-    int B;
-    int act_kind;
-    float slope;     // -alpha (even layer) or +alpha (odd layer)
-    int partial;
+    float *part;     // partial sums [nv][ldp] when the matrix is split, else null
+    long ldp;
+    Epi epi;
 };
 
-__device__ __forceinline__ void finish_row(const FwdArgs &a, long row, int c, float4 z)
-{
-    float4 r = z;
-    if (a.act_kind != 0) {
-        unsigned nib = (z.x > 0.f ? 1u : 0u) | (z.y > 0.f ? 2u : 0u) | (z.z > 0.f ? 4u : 0u) | (z.w > 0.f ? 8u : 0u);
-        a.mask[row * a.ldm + (c >> 2)] = (uint8_t)nib;
-        r.x = z.x > 0.f ? z.x : a.slope * z.x;
-        r.y = z.y > 0.f ? z.y : a.slope * z.y;
-        r.z = z.z > 0.f ? z.z : a.slope * z.z;
-        r.w = z.w > 0.f ? z.w : a.slope * z.w;
-    }
-    store_row4(a.out + row * a.ldo, c, a.B, r);
-}
-
-template <int G>
+template <int G, int U>
 __global__ __launch_bounds__(BLOCK) void fwd_kernel(FwdArgs a)
 {
-    constexpr int U = UNROLL;
     const int lane = threadIdx.x % G;
     const long v = (long)blockIdx.x * (BLOCK / G) + threadIdx.x / G;
     const int c = (blockIdx.y * G + lane) * 4;
-    if (v >= a.nv || c >= a.B) return;
+    if (v >= a.nv || c >= a.epi.B) return;
     const int p0 = a.vptr[v], p1 = a.vptr[v + 1];
     const float *xb = a.x + c;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 acc = zero4();
     for (int p = p0; p < p1; p += U) {
         int cc[U];
         float ww[U];
@@ -109,88 +157,114 @@ __global__ __launch_bounds__(BLOCK) void fwd_kernel(FwdArgs a)
             acc.w = fmaf(ww[u], xv[u].w, acc.w);
         }
     }
-    if (a.partial) {
-        st4(a.out + v * a.ldo + c, acc);
+    if (a.part) {
+        st4(a.part + v * a.ldp + c, acc);
         return;
     }
-    const long row = a.v2row ? a.v2row[v] : v;
-    const float b = a.bias ? a.bias[row] : 0.f;
-    finish_row(a, row, c, make_float4(acc.x + b, acc.y + b, acc.z + b, acc.w + b));
+    finish<G>(a.epi, a.v2row ? a.v2row[v] : v, c, true, acc, lane, 0);   // EPI_FWD: no cross-lane step
 }
 
-// Split matrices only: adds the partial sums of a row's virtual rows in order, then finishes the
-// row (bias, activation, sign mask).  One group per row.
+// ------------------------------------------------------------------------------------------------
+// Split matrices: add the partial sums of a row's virtual rows in a fixed order, then finish the row.
+// fix_kernel: one group per row (matrices with many rows, few of them split).
+// fix_block_kernel: one 1024-thread block per row (narrow matrices: 2 or 10 rows of thousands of
+// partial sums); groups stride over the row's virtual rows, then group 0 adds the group sums in order.
+// ------------------------------------------------------------------------------------------------
 struct FixArgs {
     const int *rvptr;
     int n_rows;
     const float *part;
     long ldp;
-    FwdArgs f;
+    Epi epi;
 };
+
+__device__ __forceinline__ float4 sum_partials(const float *part, long ldp, int c, int v0, int v1, int stride)
+{
+    float4 acc = zero4();
+    int v = v0;
+    for (; v + 3 * stride < v1; v += 4 * stride) {
+        const float4 t0 = ld4(part + (long)v * ldp + c), t1 = ld4(part + (long)(v + stride) * ldp + c);
+        const float4 t2 = ld4(part + (long)(v + 2 * stride) * ldp + c), t3 = ld4(part + (long)(v + 3 * stride) * ldp + c);
+        acc.x = (((acc.x + t0.x) + t1.x) + t2.x) + t3.x;
+        acc.y = (((acc.y + t0.y) + t1.y) + t2.y) + t3.y;
+        acc.z = (((acc.z + t0.z) + t1.z) + t2.z) + t3.z;
+        acc.w = (((acc.w + t0.w) + t1.w) + t2.w) + t3.w;
+    }
+    for (; v < v1; v += stride) {
+        const float4 t = ld4(part + (long)v * ldp + c);
+        acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+    }
+    return acc;
+}
 
 template <int G>
 __global__ __launch_bounds__(BLOCK) void fix_kernel(FixArgs a)
 {
     const int lane = threadIdx.x % G;
     const long row = (long)blockIdx.x * (BLOCK / G) + threadIdx.x / G;
-    const int c = (blockIdx.y * G + lane) * 4;
-    if (row >= a.n_rows || c >= a.f.B) return;
+    if (row >= a.n_rows) return;   // whole groups leave together
     const int v0 = a.rvptr[row], v1 = a.rvptr[row + 1];
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    int v = v0;
-    for (; v + 4 <= v1; v += 4) {
-        float4 t0 = ld4(a.part + (long)(v + 0) * a.ldp + c), t1 = ld4(a.part + (long)(v + 1) * a.ldp + c);
-        float4 t2 = ld4(a.part + (long)(v + 2) * a.ldp + c), t3 = ld4(a.part + (long)(v + 3) * a.ldp + c);
-        acc.x = ((acc.x + t0.x) + t1.x) + t2.x + t3.x;
-        acc.y = ((acc.y + t0.y) + t1.y) + t2.y + t3.y;
-        acc.z = ((acc.z + t0.z) + t1.z) + t2.z + t3.z;
-        acc.w = ((acc.w + t0.w) + t1.w) + t2.w + t3.w;
+    for (int tile = 0; tile * 4 * G < a.epi.B; ++tile) {
+        const int c = (tile * G + lane) * 4;
+        const bool active = c < a.epi.B;
+        float4 acc = zero4();
+        if (active) acc = sum_partials(a.part, a.ldp, c, v0, v1, 1);
+        finish<G>(a.epi, row, c, active, acc, lane, tile);
     }
-    for (; v < v1; ++v) {
-        float4 t = ld4(a.part + (long)v * a.ldp + c);
-        acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+}
+
+template <int G>
+__global__ __launch_bounds__(FIX_BLOCK) void fix_block_kernel(FixArgs a)
+{
+    constexpr int NG = FIX_BLOCK / G;
+    __shared__ float4 sh[FIX_BLOCK];
+    const int lane = threadIdx.x % G, grp = threadIdx.x / G;
+    const long row = blockIdx.x;
+    const int v0 = a.rvptr[row], v1 = a.rvptr[row + 1];
+    for (int tile = 0; tile * 4 * G < a.epi.B; ++tile) {
+        const int c = (tile * G + lane) * 4;
+        const bool active = c < a.epi.B;
+        float4 acc = zero4();
+        if (active) acc = sum_partials(a.part, a.ldp, c, v0 + grp, v1, NG);
+        sh[threadIdx.x] = acc;
+        __syncthreads();
+        if (grp == 0) {
+            float4 tot = sh[lane];
+            for (int g = 1; g < NG; ++g) {
+                const float4 t = sh[g * G + lane];
+                tot.x += t.x; tot.y += t.y; tot.z += t.z; tot.w += t.w;
+            }
+            finish<G>(a.epi, row, c, active, tot, lane, tile);
+        }
+        __syncthreads();
     }
-    const float b = a.f.bias ? a.f.bias[row] : 0.f;
-    finish_row(a.f, row, c, make_float4(acc.x + b, acc.y + b, acc.z + b, acc.w + b));
 }
 
 // ------------------------------------------------------------------------------------------------
-// dz = grad_a * f_l'(z), grad_bias = row sums of dz.  One group per row, tiles of 4*G columns.
-// Columns B .. roundup4(B)-1 of dz are written as zeros so that later float4 gathers are clean.
+// dz = grad_a * f_l'(z), grad_bias = row sums of dz (layers whose consumer did not hand dz over).
+// One group per row, tiles of 4*G columns.
 // ------------------------------------------------------------------------------------------------
 template <int G>
-__global__ __launch_bounds__(BLOCK) void actgrad_kernel(const float *ga, long ldg, const uint8_t *mask, long ldm,
-                                                       float *dz, long ldz, float *gb, int n_out, int B,
-                                                       int act_kind, float slope)
+__global__ __launch_bounds__(BLOCK) void actgrad_kernel(const float *ga, long ldg, int n_out, Epi e)
 {
     const int lane = threadIdx.x % G;
     const long row = (long)blockIdx.x * (BLOCK / G) + threadIdx.x / G;
     if (row >= n_out) return;   // whole groups leave together
-    float sum = 0.f;
-    for (int c = lane * 4; c < B; c += 4 * G) {
-        float4 g;
-        if (c + 3 < B) {
-            g = ld4(ga + row * ldg + c);
-        } else {
-            g.x = ga[row * ldg + c];
-            g.y = (c + 1 < B) ? ga[row * ldg + c + 1] : 0.f;
-            g.z = (c + 2 < B) ? ga[row * ldg + c + 2] : 0.f;
-            g.w = 0.f;
+    for (int tile = 0; tile * 4 * G < e.B; ++tile) {
+        const int c = (tile * G + lane) * 4;
+        const bool active = c < e.B;
+        float4 g = zero4();
+        if (active) {
+            if (c + 3 < e.B) {
+                g = ld4(ga + row * ldg + c);
+            } else {
+                g.x = ga[row * ldg + c];
+                g.y = (c + 1 < e.B) ? ga[row * ldg + c + 1] : 0.f;
+                g.z = (c + 2 < e.B) ? ga[row * ldg + c + 2] : 0.f;
+            }
         }
-        if (act_kind != 0) {
-            const unsigned nib = mask[row * ldm + (c >> 2)];
-            g.x = g.x * ((nib & 1u) ? 1.f : slope);
-            g.y = g.y * ((nib & 2u) ? 1.f : slope);
-            g.z = g.z * ((nib & 4u) ? 1.f : slope);
-            g.w = g.w * ((nib & 8u) ? 1.f : slope);
-            g = clip4(g, c, B);
-        }
-        st4(dz + row * ldz + c, g);
-        sum += (g.x + g.y) + (g.z + g.w);
+        finish<G>(e, row, c, active, g, lane, tile);
     }
-#pragma unroll
-    for (int m = G / 2; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, G);
-    if (lane == 0) gb[row] = sum;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -201,9 +275,9 @@ __global__ __launch_bounds__(BLOCK) void actgrad_kernel(const float *ga, long ld
 //       grad[q]    = <dz[j], x[i]>            (SDDMM restricted to the pattern)
 //   SPMM = false (first layer; runs over CSR, one group per output neuron j):
 //       holds dz[j], gathers x[i], grad[p] = <dz[j], x[i]>.
-// The U dot products of a chunk are reduced together: three exchange steps fold 8 values per lane
-// into one (lane l keeps the sum for entry l & 7), the remaining log2(G/8) steps are plain
-// butterflies, so a chunk costs 7 + log2(G/8) cross-lane moves instead of 8 * log2(G).
+// The U dot products of a chunk are reduced together: log2(U) exchange steps fold U values per lane
+// into one (lane l keeps the sum for entry l % U), the remaining log2(G/U) steps are plain
+// butterflies, so a chunk of 8 costs 7 + log2(G/8) cross-lane moves instead of 8 * log2(G).
 // ------------------------------------------------------------------------------------------------
 struct BwdArgs {
     const int *vptr;
@@ -216,20 +290,22 @@ struct BwdArgs {
     const float *gath;
     long ldga;
     float *g;        // per stored entry, in the order of this orientation
-    float *out;      // SPMM result rows [n][ldo], or partial sums [nv][ldo]
-    long ldo;
+    float *part;     // SPMM partial sums [nv][ldp] when the matrix is split, else null
+    long ldp;
     int B;
-    int partial;
+    int ragged;      // B % 4 != 0
+    Epi epi;         // SPMM, not split: what to do with the finished grad_x row
 };
 
-template <int G>
-__device__ __forceinline__ float reduce8(float (&s)[8], int lane)
+template <int G, int U>
+__device__ __forceinline__ float reduce_chunk(float (&s)[U], int lane)
 {
+    constexpr int LOGU = U == 8 ? 3 : U == 4 ? 2 : 1;
 #pragma unroll
-    for (int m = 0; m < 3; ++m) {
+    for (int m = 0; m < LOGU; ++m) {
         const bool up = (lane >> m) & 1;
 #pragma unroll
-        for (int t = 0; t < (4 >> m); ++t) {
+        for (int t = 0; t < (U >> (m + 1)); ++t) {
             const float lo = s[2 * t], hi = s[2 * t + 1];
             const float send = up ? lo : hi;
             const float keep = up ? hi : lo;
@@ -238,14 +314,13 @@ __device__ __forceinline__ float reduce8(float (&s)[8], int lane)
     }
     float r = s[0];
 #pragma unroll
-    for (int m = 8; m < G; m <<= 1) r += __shfl_xor(r, m, G);
+    for (int m = U; m < G; m <<= 1) r += __shfl_xor(r, m, G);
     return r;
 }
 
-template <int G, bool SPMM, bool RAGGED>
+template <int G, int U, bool SPMM>
 __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
 {
-    constexpr int U = 8;
     const int lane = threadIdx.x % G;
     const long v = (long)blockIdx.x * (BLOCK / G) + threadIdx.x / G;
     if (v >= a.nv) return;   // whole groups leave together
@@ -254,12 +329,12 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
     for (int tile = 0; tile * 4 * G < a.B; ++tile) {
         const int c = (tile * G + lane) * 4;
         const bool active = c < a.B;
-        float4 h = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 h = zero4();
         if (active) {
             h = ld4(a.held + row * a.ldh + c);
-            if (RAGGED) h = clip4(h, c, a.B);
+            if (a.ragged) h = clip4(h, c, a.B);
         }
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 acc = zero4();
         for (int p = p0; p < p1; p += U) {
             int cc[U];
             float ww[U];
@@ -273,10 +348,10 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                xv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                xv[u] = zero4();
                 if (active) {
                     xv[u] = ld4(a.gath + (long)cc[u] * a.ldga + c);
-                    if (RAGGED) xv[u] = clip4(xv[u], c, a.B);
+                    if (a.ragged) xv[u] = clip4(xv[u], c, a.B);
                 }
             }
 #pragma unroll
@@ -289,15 +364,18 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
                 }
                 s[u] = fmaf(h.x, xv[u].x, fmaf(h.y, xv[u].y, fmaf(h.z, xv[u].z, h.w * xv[u].w)));
             }
-            const float r = reduce8<G>(s, lane);
+            const float r = reduce_chunk<G, U>(s, lane);
             if (lane < U && p + lane < p1) {
                 if (tile == 0) a.g[p + lane] = r;
                 else a.g[p + lane] += r;
             }
         }
-        if (SPMM && active) {
-            if (a.partial) st4(a.out + v * a.ldo + c, acc);
-            else store_row4(a.out + row * a.ldo, c, a.B, acc);
+        if (SPMM) {
+            if (a.part) {
+                if (active) st4(a.part + v * a.ldp + c, acc);
+            } else {
+                finish<G>(a.epi, row, c, active, acc, lane, tile);
+            }
         }
     }
 }
@@ -366,7 +444,29 @@ __global__ __launch_bounds__(BLOCK) void softmax_ce_kernel(const float *z, long 
 // host launchers
 // ------------------------------------------------------------------------------------------------
 static int group_width(int B) { return B <= 32 ? 8 : B <= 64 ? 16 : B <= 128 ? 32 : 64; }
+static int chunk_width(const SegMat &m, long nnz)
+{
+    const double mean = m.nv > 0 ? (double)nnz / (double)m.nv : 0.0;
+    return mean <= 2.5 ? 2 : mean <= 6.0 ? 4 : 8;
+}
 
+template <typename F>
+static void dispatch_gu(int G, int U, F &&f)
+{
+#define SL_CASE_U(GG)                                                                              \
+    switch (U) {                                                                                   \
+        case 2: f(std::integral_constant<int, GG>(), std::integral_constant<int, 2>()); break;     \
+        case 4: f(std::integral_constant<int, GG>(), std::integral_constant<int, 4>()); break;     \
+        default: f(std::integral_constant<int, GG>(), std::integral_constant<int, 8>()); break;    \
+    }
+    switch (G) {
+        case 8: SL_CASE_U(8) break;
+        case 16: SL_CASE_U(16) break;
+        case 32: SL_CASE_U(32) break;
+        default: SL_CASE_U(64) break;
+    }
+#undef SL_CASE_U
+}
 template <typename F>
 static void dispatch_g(int G, F &&f)
 {
@@ -378,40 +478,50 @@ static void dispatch_g(int G, F &&f)
     }
 }
 
+static unsigned groups_to_blocks(long n_groups, int G) { return (unsigned)((n_groups + BLOCK / G - 1) / (BLOCK / G)); }
+
+static Epi dz_epilogue(sl_layer *owner, int B)
+{
+    Epi e;
+    e.mode = EPI_DZ; e.out = owner->dz; e.ldo = owner->ldz; e.bias = nullptr; e.mask_w = nullptr;
+    e.mask_r = owner->mask; e.ldm = owner->ldm; e.gb = owner->grad_bias; e.act_kind = owner->cfg.act_kind;
+    e.slope = owner->cfg.act_parity == 0 ? -owner->cfg.alpha : owner->cfg.alpha; e.B = B;
+    return e;
+}
+
+static void launch_fix(sl_layer *L, const SegMat &m, const Epi &epi, int G, int kernel_id, hipStream_t s)
+{
+    FixArgs fx;
+    fx.rvptr = m.rvptr; fx.n_rows = m.n_rows; fx.part = (const float *)(L->scratch + L->cp.partial); fx.ldp = L->ldz;
+    fx.epi = epi;
+    ProfScope ps(L, kernel_id, s);
+    dispatch_g(G, [&](auto g) {
+        constexpr int GG = decltype(g)::value;
+        if (m.n_rows < 8192) hipLaunchKernelGGL(fix_block_kernel<GG>, dim3((unsigned)m.n_rows), dim3(FIX_BLOCK), 0, s, fx);
+        else hipLaunchKernelGGL(fix_kernel<GG>, dim3(groups_to_blocks(m.n_rows, GG)), dim3(BLOCK), 0, s, fx);
+    });
+}
+
 int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, int64_t lda, hipStream_t s)
 {
     const SegMat &m = L->fwd;
-    const int G = group_width(B);
+    const int G = group_width(B), U = chunk_width(m, L->nnz);
     const int tiles = (B + 4 * G - 1) / (4 * G);
     FwdArgs f;
     f.vptr = m.vptr; f.v2row = m.v2row; f.nv = m.nv; f.idx = m.idx; f.w = L->val; f.x = x; f.ldx = ldx;
-    f.bias = L->bias; f.out = a; f.ldo = lda; f.mask = L->mask; f.ldm = L->ldm; f.B = B;
-    f.act_kind = L->cfg.act_kind; f.slope = L->cfg.act_parity == 0 ? -L->cfg.alpha : L->cfg.alpha;
-    f.partial = 0;
-    if (!m.split) {
-        dispatch_g(G, [&](auto g) {
-            constexpr int GG = decltype(g)::value;
-            dim3 grid((unsigned)((m.nv + BLOCK / GG - 1) / (BLOCK / GG)), (unsigned)tiles);
-            ProfScope ps(L, K_FWD, s);
-            hipLaunchKernelGGL(fwd_kernel<GG>, grid, dim3(BLOCK), 0, s, f);
-        });
-    } else {
-        FwdArgs pa = f;
-        pa.partial = 1; pa.out = (float *)(L->scratch + L->cp.partial); pa.ldo = L->ldz;
-        FixArgs fx;
-        fx.rvptr = m.rvptr; fx.n_rows = m.n_rows; fx.part = pa.out; fx.ldp = L->ldz; fx.f = f;
-        dispatch_g(G, [&](auto g) {
-            constexpr int GG = decltype(g)::value;
-            dim3 grid((unsigned)((m.nv + BLOCK / GG - 1) / (BLOCK / GG)), (unsigned)tiles);
-            {
-                ProfScope ps(L, K_FWD, s);
-                hipLaunchKernelGGL(fwd_kernel<GG>, grid, dim3(BLOCK), 0, s, pa);
-            }
-            dim3 grid2((unsigned)((m.n_rows + BLOCK / GG - 1) / (BLOCK / GG)), (unsigned)tiles);
-            ProfScope ps(L, K_FWD_FIX, s);
-            hipLaunchKernelGGL(fix_kernel<GG>, grid2, dim3(BLOCK), 0, s, fx);
+    f.part = m.split ? (float *)(L->scratch + L->cp.partial) : nullptr; f.ldp = L->ldz;
+    Epi &e = f.epi;
+    e.mode = EPI_FWD; e.out = a; e.ldo = lda; e.bias = L->bias; e.mask_w = L->mask; e.mask_r = nullptr; e.ldm = L->ldm;
+    e.gb = nullptr; e.act_kind = L->cfg.act_kind; e.slope = L->cfg.act_parity == 0 ? -L->cfg.alpha : L->cfg.alpha; e.B = B;
+    {
+        ProfScope ps(L, K_FWD, s);
+        dispatch_gu(G, U, [&](auto g, auto u) {
+            constexpr int GG = decltype(g)::value, UU = decltype(u)::value;
+            dim3 grid(groups_to_blocks(m.nv, GG), (unsigned)tiles);
+            hipLaunchKernelGGL((fwd_kernel<GG, UU>), grid, dim3(BLOCK), 0, s, f);
         });
     }
+    if (m.split) launch_fix(L, m, e, G, K_FWD_FIX, s);
     SL_HIP(L, hipGetLastError());
     return SL_OK;
 }
@@ -420,53 +530,52 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
                     int64_t ldgx, hipStream_t s)
 {
     const int G = group_width(B);
-    const float slope = L->cfg.act_parity == 0 ? -L->cfg.alpha : L->cfg.alpha;
     const int n_out = (int)L->cfg.n_out;
-    dispatch_g(G, [&](auto g) {
-        constexpr int GG = decltype(g)::value;
-        dim3 grid((unsigned)((n_out + BLOCK / GG - 1) / (BLOCK / GG)));
+    if (L->dz_ready != B) {
+        const Epi e = dz_epilogue(L, B);
         ProfScope ps(L, K_ACTGRAD, s);
-        hipLaunchKernelGGL(actgrad_kernel<GG>, grid, dim3(BLOCK), 0, s, ga, (long)ldg, L->mask, (long)L->ldm, L->dz,
-                           (long)L->ldz, L->grad_bias, n_out, B, L->cfg.act_kind, slope);
-    });
-    const bool ragged = (B % 4) != 0;
+        dispatch_g(G, [&](auto g) {
+            constexpr int GG = decltype(g)::value;
+            hipLaunchKernelGGL(actgrad_kernel<GG>, dim3(groups_to_blocks(n_out, GG)), dim3(BLOCK), 0, s, ga, (long)ldg,
+                               n_out, e);
+        });
+    }
+    L->dz_ready = 0;
     BwdArgs b;
-    b.B = B; b.g = L->grad; b.partial = 0;
+    b.B = B; b.g = L->grad; b.ragged = (B % 4) != 0; b.part = nullptr; b.ldp = L->ldz;
     if (L->has_csc) {
         const SegMat &m = L->bwd;
+        const int U = chunk_width(m, L->nnz);
         b.vptr = m.vptr; b.v2row = m.v2row; b.nv = m.nv; b.idx = m.idx; b.w = L->valT;
-        b.held = x; b.ldh = ldx; b.gath = L->dz; b.ldga = L->ldz; b.out = gx; b.ldo = ldgx;
-        if (m.split) { b.partial = 1; b.out = (float *)(L->scratch + L->cp.partial); b.ldo = L->ldz; }
-        dispatch_g(G, [&](auto g) {
-            constexpr int GG = decltype(g)::value;
-            dim3 grid((unsigned)((m.nv + BLOCK / GG - 1) / (BLOCK / GG)));
-            {
-                ProfScope ps(L, K_BWD_FUSED, s);
-                if (ragged) hipLaunchKernelGGL((bwd_kernel<GG, true, true>), grid, dim3(BLOCK), 0, s, b);
-                else hipLaunchKernelGGL((bwd_kernel<GG, true, false>), grid, dim3(BLOCK), 0, s, b);
-            }
-            if (m.split) {
-                FixArgs fx;
-                fx.rvptr = m.rvptr; fx.n_rows = m.n_rows; fx.part = b.out; fx.ldp = L->ldz;
-                fx.f.vptr = nullptr; fx.f.v2row = nullptr; fx.f.nv = 0; fx.f.idx = nullptr; fx.f.w = nullptr;
-                fx.f.x = nullptr; fx.f.ldx = 0; fx.f.bias = nullptr; fx.f.out = gx; fx.f.ldo = ldgx;
-                fx.f.mask = nullptr; fx.f.ldm = 0; fx.f.B = B; fx.f.act_kind = 0; fx.f.slope = 0.f; fx.f.partial = 0;
-                const int tiles = (B + 4 * GG - 1) / (4 * GG);
-                dim3 grid2((unsigned)((m.n_rows + BLOCK / GG - 1) / (BLOCK / GG)), (unsigned)tiles);
-                ProfScope ps(L, K_BWD_FIX, s);
-                hipLaunchKernelGGL(fix_kernel<GG>, grid2, dim3(BLOCK), 0, s, fx);
-            }
-        });
+        b.held = x; b.ldh = ldx; b.gath = L->dz; b.ldga = L->ldz;
+        if (m.split) b.part = (float *)(L->scratch + L->cp.partial);
+        sl_layer *P = gx ? nullptr : L->producer;
+        if (P) {   // hand dz straight to the layer that produced x
+            b.epi = dz_epilogue(P, B);
+        } else {
+            Epi &e = b.epi;
+            e.mode = EPI_PLAIN; e.out = gx; e.ldo = ldgx; e.bias = nullptr; e.mask_w = nullptr; e.mask_r = nullptr;
+            e.ldm = 0; e.gb = nullptr; e.act_kind = 0; e.slope = 0.f; e.B = B;
+        }
+        {
+            ProfScope ps(L, K_BWD_FUSED, s);
+            dispatch_gu(G, U, [&](auto g, auto u) {
+                constexpr int GG = decltype(g)::value, UU = decltype(u)::value;
+                hipLaunchKernelGGL((bwd_kernel<GG, UU, true>), dim3(groups_to_blocks(m.nv, GG)), dim3(BLOCK), 0, s, b);
+            });
+        }
+        if (m.split) launch_fix(L, m, b.epi, G, K_BWD_FIX, s);
+        if (P) P->dz_ready = B;
     } else {
         const SegMat &m = L->fwd;
+        const int U = chunk_width(m, L->nnz);
         b.vptr = m.vptr; b.v2row = m.v2row; b.nv = m.nv; b.idx = m.idx; b.w = nullptr;
-        b.held = L->dz; b.ldh = L->ldz; b.gath = x; b.ldga = ldx; b.out = nullptr; b.ldo = 0;
-        dispatch_g(G, [&](auto g) {
-            constexpr int GG = decltype(g)::value;
-            dim3 grid((unsigned)((m.nv + BLOCK / GG - 1) / (BLOCK / GG)));
-            ProfScope ps(L, K_SDDMM, s);
-            if (ragged) hipLaunchKernelGGL((bwd_kernel<GG, false, true>), grid, dim3(BLOCK), 0, s, b);
-            else hipLaunchKernelGGL((bwd_kernel<GG, false, false>), grid, dim3(BLOCK), 0, s, b);
+        b.held = L->dz; b.ldh = L->ldz; b.gath = x; b.ldga = ldx;
+        b.epi = Epi();
+        ProfScope ps(L, K_SDDMM, s);
+        dispatch_gu(G, U, [&](auto g, auto u) {
+            constexpr int GG = decltype(g)::value, UU = decltype(u)::value;
+            hipLaunchKernelGGL((bwd_kernel<GG, UU, false>), dim3(groups_to_blocks(m.nv, GG)), dim3(BLOCK), 0, s, b);
         });
     }
     SL_HIP(L, hipGetLastError());

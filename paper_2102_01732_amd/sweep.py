@@ -1,0 +1,100 @@
+"""Single-layer kernel sweep: one n x n Erdos-Renyi layer (n = 262 144), epsilon in {1,4,16,64},
+batch in {32,128,512,1024}; times the forward SpMM, the fused backward (transposed SpMM + SDDMM),
+the SDDMM alone and one SET evolution, each against the HBM roofline.
+
+    python -m paper_2102_01732_amd.sweep [--n 262144] [--reps 20] [--out profiles/sweep.md]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import time
+
+import torch
+
+from . import binding, workloads as wl
+
+PEAK = 8000.0
+
+
+def bytes_model(kernel: str, nnz: int, n: int, B: int):
+    """(per-connection algorithmic bytes, each-operand-once bytes) of one launch."""
+    row = 4 * B
+    if kernel == "forward_spmm":
+        fixed = 8 * nnz + n * (row + B // 4 + 8)
+    elif kernel == "backward_fused":
+        fixed = 12 * nnz + n * (2 * row + 4)
+    else:  # sddmm
+        fixed = 8 * nnz + n * (row + 4)
+    return fixed + row * nnz, fixed + row * n
+
+
+def run(n: int, reps: int, eps_list, batch_list):
+    rows = []
+    maxB = max(batch_list)
+    x = torch.randn((n, maxB), device="cuda")
+    ga = torch.randn((n, maxB), device="cuda")
+    a = torch.empty((n, maxB), device="cuda")
+    gx = torch.empty((n, maxB), device="cuda")
+    for eps in eps_list:
+        spec = wl.sweep_layer(eps, n)
+        mk = lambda need: binding.SparseLayer(binding.make_config(
+            n, n, nnz=spec.nnz, act_kind=1, act_parity=0, alpha=0.6, init_limit=spec.init_limit, seed=wl.DEFAULT_SEED,
+            layer_id=0, max_batch=maxB, need_input_grad=need))
+        full, first = mk(True), mk(False)
+        for B in batch_list:
+            for layer in (full, first):
+                for it in range(3 + reps):
+                    if it == 3:
+                        layer.profile_begin()
+                    layer.forward(x, B, a)
+                    layer.backward(x, ga, B, gx if layer is full else None)
+                prof = layer.profile_end()
+                for name in (("forward_spmm", "backward_fused") if layer is full else ("sddmm",)):
+                    cnt, ms = prof[name]
+                    t = ms / cnt
+                    alg, comp = bytes_model(name, spec.nnz, n, B)
+                    rows.append(dict(eps=eps, B=B, kernel=name, nnz=spec.nnz, ms=t, gbs=alg / t / 1e6,
+                                     frac=alg / t / 1e6 / PEAK, compulsory_gbs=comp / t / 1e6))
+        gen = 0
+        ts = []
+        for it in range(1 + 3):
+            gen += 1
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            full.evolve(0.3, gen)
+            torch.cuda.synchronize()
+            ts.append((time.perf_counter() - t0) * 1e3)
+        t = sorted(ts[1:])[1]
+        rows.append(dict(eps=eps, B=0, kernel="evolve(zeta=0.3)", nnz=spec.nnz, ms=t, gbs=16 * spec.nnz / t / 1e6,
+                         frac=16 * spec.nnz / t / 1e6 / PEAK, compulsory_gbs=16 * spec.nnz / t / 1e6))
+        full.close()
+        first.close()
+    return rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--n", type=int, default=wl.SWEEP_N)
+    ap.add_argument("--reps", type=int, default=20)
+    ap.add_argument("--eps", type=int, nargs="*", default=list(wl.SWEEP_EPSILON))
+    ap.add_argument("--batch", type=int, nargs="*", default=list(wl.SWEEP_BATCH))
+    ap.add_argument("--out", default=None)
+    args = ap.parse_args()
+    rows = run(args.n, args.reps, args.eps, args.batch)
+    lines = [f"# single-layer sweep, n_in = n_out = {args.n}, one MI355X, {args.reps} timed repeats (HIP events per kernel)",
+             "# GB/s = per-connection algorithmic bytes / time (each stored connection fetches its own 4*B-byte row);",
+             "# compulsory GB/s = each operand once.  evolve: 16 B/connection nominal.",
+             "| eps | B | kernel | nnz | ms | GB/s | frac of 8 TB/s | compulsory GB/s |", "|---|---|---|---|---|---|---|---|"]
+    for r in rows:
+        lines.append(f"| {r['eps']} | {r['B'] or '-'} | {r['kernel']} | {r['nnz']} | {r['ms']:.4f} | {r['gbs']:.0f} | "
+                     f"{r['frac']:.3f} | {r['compulsory_gbs']:.0f} |")
+    text = "\n".join(lines) + "\n"
+    print(text)
+    if args.out:
+        open(args.out, "w").write(text)
+    print(json.dumps(rows))
+
+
+if __name__ == "__main__":
+    main()

@@ -72,10 +72,8 @@ def test_one_million_neuron_training_step(setup):
     yd = torch.from_numpy(y).cuda()
     net = make_net(binding, w)
     zL = net.forward(x0, B)
-    binding.softmax_ce(zL, yd, B, net.n_classes, net.grads[-1], net.loss_sum)
-    for li in range(len(net.layers) - 1, -1, -1):
-        xin = x0 if li == 0 else net.acts[li - 1]
-        net.layers[li].backward(xin, net.grads[li], B, net.grads[li - 1] if li > 0 else None)
+    binding.softmax_ce(zL, yd, B, net.n_classes, net.grad_out, net.loss_sum)
+    net.backward(x0, B)
     stride = golden["val_stride"]
     grads = [G.export_grad() for G in net.layers]
     for G in net.layers:

@@ -351,3 +351,45 @@ def test_image_shaped_networks_first_steps(gpu, oracle, name, steps):
     w = wl.WORKLOADS[name]
     net, onet, olayers = run_network(gpu, oracle, w, steps, tol_first=1e-4, tol_end=3e-4)
     net.close()
+
+
+# ------------------------------------------------------------------------------------------ chained layers
+@pytest.mark.parametrize("dims,nnz,B,max_batch", [
+    ((300, 500, 200), (4000, 5000), 128, 128),
+    ((300, 500, 200), (4000, 5000), 77, 128),        # ragged batch
+    ((300, 6, 2000), (1800, 12000), 96, 128),        # long columns: the consumer's CSC side is split
+    ((200, 400, 2), (3000, 800), 300, 512),          # batch tiles; narrow dense consumer
+])
+def test_linked_backward_equals_unlinked(gpu, oracle, dims, nnz, B, max_batch):
+    """Handing dz to the producer inside the consumer's backward kernel must give exactly what the
+    separate path (grad_x buffer, then the producer's own activation-derivative pass) gives."""
+    import torch
+    rng = np.random.default_rng(7)
+    mk = lambda li, need: gpu.SparseLayer(gpu.make_config(dims[li], dims[li + 1], nnz=nnz[li], act_kind=1,
+                                                           act_parity=li % 2, alpha=0.6, init_limit=0.2, seed=3,
+                                                           layer_id=li, max_batch=max_batch, need_input_grad=need))
+    ld = (B + 3) // 4 * 4
+    x = dev(torch, pad_cols(rng.standard_normal((dims[0], B)).astype(np.float32), ld))
+    ga = dev(torch, pad_cols(rng.standard_normal((dims[2], B)).astype(np.float32), ld))
+    results = []
+    for linked in (False, True):
+        P, C = mk(0, False), mk(1, True)
+        a1 = torch.zeros((dims[1], ld), device="cuda")
+        a2 = torch.zeros((dims[2], ld), device="cuda")
+        P.forward(x, B, a1)
+        C.forward(a1, B, a2)
+        if linked:
+            C.link_producer(P)
+            C.backward(a1, ga, B, None)
+            P.backward(x, None, B, None)
+        else:
+            g1 = torch.zeros((dims[1], ld), device="cuda")
+            C.backward(a1, ga, B, g1)
+            P.backward(x, g1, B, None)
+        results.append((P.export_grad(), C.export_grad()))
+        P.close()
+        C.close()
+    for (g_u, gb_u), (g_l, gb_l) in zip(results[0], results[1]):
+        assert np.array_equal(g_u.view(np.uint32), g_l.view(np.uint32))
+        assert np.array_equal(gb_u.view(np.uint32), gb_l.view(np.uint32))
+    assert np.abs(results[0][0][0]).max() > 0
