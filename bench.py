@@ -45,6 +45,45 @@ def algorithmic_bytes(kernel, spec, B, has_csc):
     return 0, 0
 
 
+def run_small(name, torch, np, binding, wl, dev, with_cpu):
+    """One epoch (all minibatches, last one partial) plus one evolution of a small workload."""
+    w = wl.WORKLOADS[name]
+    B, nb = w.batch, w.steps_per_epoch
+    X, y = wl.dataset(w)
+    host_blocks = wl.to_batch_blocks(X, B)
+    blocks = torch.from_numpy(host_blocks).to(dev)
+    ypad = np.zeros(nb * B, np.int32)
+    ypad[: y.size] = y
+    labels = torch.from_numpy(ypad.reshape(nb, B)).to(dev)
+    sizes = [min(B, w.n_samples - k * B) for k in range(nb)]
+    net = binding.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=B)
+    for k in range(3):
+        net.train_step(blocks[k], labels[k], sizes[k])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(nb):
+        net.train_step(blocks[k], labels[k], sizes[k])
+    net.evolve(w.zeta, 1)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    rec = dict(workload=name, dims=list(w.dims), steps=nb, value=w.n_samples / dt, unit="samples/s",
+               ms_per_step=dt / nb * 1e3, includes="one epoch + one SET evolution")
+    net.close()
+    if with_cpu:
+        from oracle import oracle as orc
+        olayers = [orc.OracleLayer(s.n_in, s.n_out, s.nnz, s.act_kind, s.act_parity, w.alpha, s.init_limit, w.lr,
+                                   w.momentum, 0.0, w.seed, s.layer_id) for s in w.layers]
+        onet = orc.OracleMLP(olayers)
+        ns = min(8, nb)
+        c0 = time.perf_counter()
+        for k in range(ns):
+            onet.train_step(host_blocks[k][:, : sizes[k]], ypad[k * B: k * B + sizes[k]])
+        c1 = time.perf_counter()
+        rec["cpu_baseline"] = dict(value=sum(sizes[:ns]) / (c1 - c0), unit="samples/s", cores=1, kind="oracle",
+                                   sample=f"first {ns} training steps")
+    return rec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,6 +93,8 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--cpu-samples", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extra-workloads", default="set_mlp_madelon,set_mlp_fmnist,set_mlp_cifar",
+                    help="comma list of further workloads timed for one epoch each and reported under `other_workloads`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -185,13 +226,22 @@ def main():
                    sample=f"one training step (forward, loss, backward, update) on the first {ns} samples of "
                           f"minibatch 0 at the full layer shapes; {c1 - c0:.1f} s; evolution not included")
 
+    # ---- the smaller workloads, one epoch (+ evolution) each, for the record
+    others = []
+    net.close()
+    del net, blocks, labels
+    torch.cuda.empty_cache()
+    for name in [n for n in args.extra_workloads.split(",") if n and n != args.workload]:
+        others.append(run_small(name, torch, np, binding, wl, dev, not args.no_cpu_baseline))
+
     out = dict(metric="sparse-MLP train samples/s", value=value, unit="samples/s", n_gpus=1, steps=K,
                warmup=args.warmup, ms_per_step=elapsed / K * 1e3, higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="f32", data=data_note,
                config=dict(workload=args.workload, dims=list(w.dims), epsilon=w.epsilon, batch=B,
                            nnz=[s.nnz for s in w.layers], alpha=w.alpha, zeta=w.zeta,
                            evolutions_in_timed_region=K // n_blocks, parallelism="single GPU"),
-               roofline=roofline, cpu_baseline=cpu, evolve_ms_all_layers=evolve_ms, kernels=kernels[:12])
+               roofline=roofline, cpu_baseline=cpu, evolve_ms_all_layers=evolve_ms, kernels=kernels[:12],
+               other_workloads=others)
     print(json.dumps(out))
 
 
