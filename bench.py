@@ -231,7 +231,7 @@ def main():
     net.close()
     del net, blocks, labels
     torch.cuda.empty_cache()
-    for name in [n for n in args.extra_workloads.split(",") if n and n != args.workload]:
+    for name in [n for n in args.extra_workloads.split(",") if n in wl.WORKLOADS and n != args.workload]:
         others.append(run_small(name, torch, np, binding, wl, dev, not args.no_cpu_baseline))
 
     out = dict(metric="sparse-MLP train samples/s", value=value, unit="samples/s", n_gpus=1, steps=K,
