@@ -226,6 +226,19 @@ def main():
                    sample=f"one training step (forward, loss, backward, update) on the first {ns} samples of "
                           f"minibatch 0 at the full layer shapes; {c1 - c0:.1f} s; evolution not included")
 
+    # ---- Importance Pruning (eq. 4 + Algorithm 2) on the first 10^6 x 10^6 layer: weakest 10 % of the neurons
+    L1 = net.layers[1] if len(net.layers) > 1 else net.layers[0]
+    torch.cuda.synchronize()
+    ti0 = time.perf_counter()
+    imp = L1.importance()
+    ti1 = time.perf_counter()
+    thr = float(np.quantile(imp.astype(np.float64), 0.10))
+    removed = L1.importance_prune(thr)
+    torch.cuda.synchronize()
+    ti2 = time.perf_counter()
+    importance = dict(layer=1, importance_ms=(ti1 - ti0) * 1e3, prune_ms=(ti2 - ti1) * 1e3, threshold=thr,
+                      removed_connections=removed, nnz_after=L1.nnz)
+
     # ---- the smaller workloads, one epoch (+ evolution) each, for the record
     others = []
     net.close()
@@ -241,7 +254,7 @@ def main():
                            nnz=[s.nnz for s in w.layers], alpha=w.alpha, zeta=w.zeta,
                            evolutions_in_timed_region=K // n_blocks, parallelism="single GPU"),
                roofline=roofline, cpu_baseline=cpu, evolve_ms_all_layers=evolve_ms, kernels=kernels[:12],
-               other_workloads=others)
+               importance_pruning=importance, other_workloads=others)
     print(json.dumps(out))
 
 

@@ -117,6 +117,17 @@ int sparse_layer_update(sl_layer *layer, void *hip_stream);
  * view.  nnz is unchanged.  k = floor(zeta*nnz + 0.5) in double.  Synchronises the stream. */
 int sparse_layer_evolve(sl_layer *layer, double zeta, uint64_t generation, void *hip_stream);
 
+/* Neuron importance, eq. (4): importance[j] = sum over the stored incoming connections of neuron j of
+ * |Wt[j,i]|, added in fp32 in stored order.  importance_host: host array of n_out floats.
+ * Synchronises the layer's last stream. */
+int sparse_layer_importance(sl_layer *layer, float *importance_host);
+
+/* Importance Pruning of Algorithm 2: removes ALL incoming connections of every neuron whose
+ * importance (as above) is < threshold and compacts CSR, CSC view and velocities.  nnz shrinks (the
+ * buffers keep their size); later evolutions preserve the reduced nnz.  *removed (host, may be
+ * NULL) receives the number of removed connections.  Synchronises the stream. */
+int sparse_layer_importance_prune(sl_layer *layer, float threshold, int64_t *removed, void *hip_stream);
+
 int sparse_layer_destroy(sl_layer *layer);
 
 /* Softmax + cross-entropy over C output neurons (the loss is unnamed in the paper).

@@ -74,6 +74,8 @@ def lib():
         L.or_softmax_ce.restype = c.c_double
         L.or_importance.argtypes = [c.c_int64, _i32p, _f32p, _f32p]
         L.or_importance.restype = None
+        L.or_importance_f32.argtypes = [c.c_int64, _i32p, _f32p, _f32p]
+        L.or_importance_f32.restype = None
         _lib = L
     return _lib
 
@@ -252,6 +254,30 @@ class OracleLayer:
         out = np.zeros(self.n_out, dtype=np.float32)
         lib().or_importance(self.n_out, self.rowptr, self.val, out)
         return out
+
+    def importance_f32(self) -> np.ndarray:
+        out = np.zeros(self.n_out, dtype=np.float32)
+        lib().or_importance_f32(self.n_out, self.rowptr, self.val if self.nnz else np.zeros(1, np.float32), out)
+        return out
+
+    def importance_prune(self, threshold: float) -> int:
+        """Algorithm 2, Importance Pruning: remove all incoming connections of neurons whose importance
+        (eq. 4) is below the threshold.  nnz shrinks; returns the number of removed connections."""
+        gone_rows = self.importance_f32() < np.float32(threshold)
+        rows = np.repeat(np.arange(self.n_out), np.diff(self.rowptr))
+        keep = ~gone_rows[rows]
+        removed = int((~keep).sum())
+        counts = np.diff(self.rowptr).astype(np.int64)
+        counts[gone_rows] = 0
+        rowptr = np.zeros(self.n_out + 1, dtype=np.int64)
+        np.cumsum(counts, out=rowptr[1:])
+        self.rowptr = rowptr.astype(np.int32)
+        self.colidx = np.ascontiguousarray(self.colidx[keep])
+        self.val = np.ascontiguousarray(self.val[keep])
+        self.vel = np.ascontiguousarray(self.vel[keep])
+        self.grad_val = np.zeros_like(self.val)
+        self.z = None
+        return removed
 
     def dense(self) -> np.ndarray:
         """Wt as a dense float64 matrix with zeros (for brute-force checks only)."""

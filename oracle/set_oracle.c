@@ -32,6 +32,8 @@
  *   or_prune_select       Algorithm 2's removal step (magnitude based).
  *   or_softmax_ce         softmax + cross-entropy loss and its gradient (loss unnamed in the
  *                         paper; this is the reading used throughout).
+ *   or_importance(_f32)   neuron importance, eq. (4); Importance Pruning of Algorithm 2 removes the
+ *                         incoming connections of neurons whose importance is below a threshold.
  *
  * Build: gcc -O2 -ffp-contract=off -fPIC -shared set_oracle.c -o liboracle.so -lm
  */
@@ -374,6 +376,18 @@ double or_softmax_ce(const float *z, int64_t ldz, const int32_t *y, int32_t B, i
         loss -= ((double)z[(int64_t)y[b] * ldz + b] - m) - log(s);
     }
     return loss / (double)B;
+}
+
+/* Neuron importance, eq. (4), evaluated in the paper's precision: fp32 additions of |w| in stored
+ * (CSR) order.  This is the value the Importance Pruning decision "I < t" of Algorithm 2 is taken
+ * on, so that the decision does not depend on who evaluates it. */
+void or_importance_f32(int64_t n_out, const int32_t *rowptr, const float *val, float *importance)
+{
+    for (int64_t j = 0; j < n_out; ++j) {
+        float s = 0.0f;
+        for (int32_t p = rowptr[j]; p < rowptr[j + 1]; ++p) s = s + fabsf(val[p]);
+        importance[j] = s;
+    }
 }
 
 /* Neuron importance, eq. (4): I_j = sum over incoming connections of |w_ij| (row sums of |Wt|). */

@@ -25,7 +25,7 @@ EXPORTS = [
     "sparse_layer_update", "sparse_layer_evolve", "sparse_layer_destroy", "sparse_loss_softmax_ce",
     "sparse_layer_nnz", "sparse_layer_export_csr", "sparse_layer_import_csr", "sparse_layer_export_grad",
     "sparse_layer_set_lr", "sparse_layer_last_error", "sparse_layer_profile_begin", "sparse_layer_profile_end",
-    "sparse_kernel_name", "sparse_layer_link_producer",
+    "sparse_kernel_name", "sparse_layer_link_producer", "sparse_layer_importance", "sparse_layer_importance_prune",
 ]
 N_KERNEL_IDS = 7
 
@@ -69,6 +69,8 @@ def lib():
         L.sparse_layer_last_error.argtypes = [vp]
         L.sparse_layer_last_error.restype = C.c_char_p
         L.sparse_layer_link_producer.argtypes = [vp, vp]
+        L.sparse_layer_importance.argtypes = [vp, vp]
+        L.sparse_layer_importance_prune.argtypes = [vp, C.c_float, C.POINTER(i64), vp]
         L.sparse_layer_profile_begin.argtypes = [vp]
         L.sparse_layer_profile_end.argtypes = [vp, vp, vp, i32]
         L.sparse_kernel_name.argtypes = [i32]
@@ -151,6 +153,18 @@ class SparseLayer:
     def evolve(self, zeta: float, generation: int):
         self._check(lib().sparse_layer_evolve(self.handle, float(zeta), int(generation), _stream()),
                     "sparse_layer_evolve")
+
+    def importance(self) -> np.ndarray:
+        out = np.zeros(self.n_out, np.float32)
+        self._check(lib().sparse_layer_importance(self.handle, out.ctypes.data), "sparse_layer_importance")
+        return out
+
+    def importance_prune(self, threshold: float) -> int:
+        removed = C.c_int64(0)
+        self._check(lib().sparse_layer_importance_prune(self.handle, float(threshold), C.byref(removed), _stream()),
+                    "sparse_layer_importance_prune")
+        self.nnz -= removed.value
+        return removed.value
 
     def set_lr(self, lr: float):
         self._check(lib().sparse_layer_set_lr(self.handle, float(lr)), "sparse_layer_set_lr")

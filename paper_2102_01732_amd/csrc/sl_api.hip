@@ -110,8 +110,11 @@ int plan_scratch(const sl_config &c, int64_t nnz, ScratchPlan *cp)
     const bool csc = (c.flags & SL_FLAG_NEED_INPUT_GRAD) != 0;
     const double M = (double)c.n_in * (double)c.n_out;
     cp->dense_mode = M <= 4.0 * (double)nnz;
-    if (cp->dense_mode) cp->w_cap = (int64_t)M;
-    else cp->w_cap = 2 * sampler_window(M, 0.0, (double)nnz);
+    // Importance Pruning can shrink nnz, which can move a dense-mode layer into the sparse mode (never
+    // the other way round); the window is sized for whichever needs more.
+    const double k_sparse = (double)nnz < floor(M / 4.0) ? (double)nnz : floor(M / 4.0);
+    cp->w_cap = 2 * sampler_window(M, 0.0, k_sparse);
+    if (cp->dense_mode && cp->w_cap < (int64_t)M) cp->w_cap = (int64_t)M;
     if (cp->w_cap < (int64_t)n) cp->w_cap = (int64_t)n;
     const size_t w = (size_t)cp->w_cap;
     // the regions of the training passes and of init/evolve never live at the same time
@@ -160,7 +163,8 @@ static int check_config(const sl_config *c, int64_t *nnz_out)
     if (nnz >= ((int64_t)1 << 30)) return SL_EOVERFLOW;
     const double M = (double)c->n_in * (double)c->n_out;
     if (M <= 4.0 * (double)nnz && M >= 2147483647.0) return SL_EOVERFLOW;
-    if (M > 4.0 * (double)nnz && 2 * sampler_window(M, 0.0, (double)nnz) >= ((int64_t)1 << 32) - 2) return SL_EOVERFLOW;
+    const double k_sparse = (double)nnz < floor(M / 4.0) ? (double)nnz : floor(M / 4.0);
+    if (2 * sampler_window(M, 0.0, k_sparse) >= ((int64_t)1 << 32) - 2) return SL_EOVERFLOW;
     *nnz_out = nnz;
     return SL_OK;
 }
@@ -336,6 +340,30 @@ int sparse_layer_evolve(sl_layer *L, double zeta, uint64_t generation, void *hip
     hipError_t e = hipStreamSynchronize(L->last_stream);
     if (e != hipSuccess) return set_err(L, SL_EHIP, "evolve: %s", hipGetErrorString(e));
     L->phase = 0;
+    return SL_OK;
+}
+
+int sparse_layer_importance(sl_layer *L, float *importance_host)
+{
+    if (!L || !importance_host) return SL_EINVAL;
+    float *imp = (float *)(L->scratch + L->cp.f0);
+    int rc = topo_importance(L, imp, L->last_stream);
+    if (rc) return rc;
+    SL_HIP(L, hipMemcpyAsync(importance_host, imp, sizeof(float) * (size_t)L->cfg.n_out, hipMemcpyDeviceToHost, L->last_stream));
+    SL_HIP(L, hipStreamSynchronize(L->last_stream));
+    return SL_OK;
+}
+
+int sparse_layer_importance_prune(sl_layer *L, float threshold, int64_t *removed, void *hip_stream)
+{
+    if (!L) return SL_EINVAL;
+    if (threshold != threshold) return set_err(L, SL_EINVAL, "threshold is NaN");
+    L->last_stream = (hipStream_t)hip_stream;
+    int rc = topo_importance_prune(L, threshold, removed, L->last_stream);
+    if (rc) return rc;
+    SL_HIP(L, hipStreamSynchronize(L->last_stream));
+    L->phase = 0;
+    L->dz_ready = 0;
     return SL_OK;
 }
 

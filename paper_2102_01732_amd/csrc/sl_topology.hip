@@ -474,6 +474,37 @@ __global__ void fill_i32_kernel(long n, int *a, int v)
 }
 
 // ------------------------------------------------------------------------------------------------
+// Importance Pruning (eq. 4 and Algorithm 2): I_j = sum of |w| over the incoming connections of
+// neuron j, added in fp32 in stored order (one thread per neuron, so that the value -- and with it
+// the decision I_j < t -- is the same whoever evaluates it); every connection of a neuron with
+// I_j < t is removed.
+// ------------------------------------------------------------------------------------------------
+__global__ void importance_kernel(int n_rows, const int *rowptr, const float *val, float *imp)
+{
+    const int r = blockIdx.x * TB + threadIdx.x;
+    if (r >= n_rows) return;
+    float s = 0.f;
+    for (int p = rowptr[r]; p < rowptr[r + 1]; ++p) s = s + fabsf(val[p]);
+    imp[r] = s;
+}
+__global__ void importance_keep_kernel(long n, int n_rows, const int *rowptr, const float *imp, float threshold,
+                                       uint32_t *keep)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p > n) return;
+    keep[p] = (p < n && !(imp[row_of(rowptr, n_rows, (int)p)] < threshold)) ? 1u : 0u;
+}
+__global__ void copy_back_kernel(long n, const int *s_col, const float *s_val, const float *s_vel, int *col, float *val,
+                                 float *vel)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p >= n) return;
+    col[p] = s_col[p];
+    val[p] = s_val[p];
+    vel[p] = s_vel[p];
+}
+
+// ------------------------------------------------------------------------------------------------
 // host orchestration
 // ------------------------------------------------------------------------------------------------
 template <typename T>
@@ -580,7 +611,9 @@ static int sample_positions(sl_layer *L, long k, long n_occ, uint32_t generation
     uint64_t *new_p = at<uint64_t>(L, L->cp.new_p);
     char *temp = at<char>(L, L->cp.temp);
     uint64_t *ks; uint32_t *vs;
-    if (L->cp.dense_mode) {
+    const bool dense_mode = (double)M <= 4.0 * (double)(n_occ + k);   // the definition's rule on the current nnz
+    if (dense_mode && (int64_t)M > L->cp.w_cap) return set_err(L, SL_ENOMEM, "dense sampler needs %llu slots", (unsigned long long)M);
+    if (dense_mode) {
         const long Ml = (long)M;
         hipLaunchKernelGGL(empty_flag_kernel, dim3(nblk(Ml + 1)), dim3(TB), 0, s, Ml, rowptr_s, s_col, n_in, f0);
         SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, f0, f1, (size_t)Ml + 1, s));
@@ -636,6 +669,46 @@ static int rebuild(sl_layer *L, long ns, long k, uint32_t generation, hipStream_
         hipLaunchKernelGGL(merge_new_kernel, dim3(nblk(k)), dim3(TB), 0, s, k, n_in, rowptr_s, s_col, new_p,
                            make_rng(L, generation), L->cfg.init_limit, L->colidx, L->val, L->vel);
     SL_HIP(L, hipGetLastError());
+    return topo_finalize(L, s);
+}
+
+int topo_importance(sl_layer *L, float *imp_dev, hipStream_t s)
+{
+    hipLaunchKernelGGL(importance_kernel, dim3(nblk(L->cfg.n_out)), dim3(TB), 0, s, (int)L->cfg.n_out, L->rowptr, L->val,
+                       imp_dev);
+    SL_HIP(L, hipGetLastError());
+    return SL_OK;
+}
+
+int topo_importance_prune(sl_layer *L, float threshold, int64_t *removed, hipStream_t s)
+{
+    const long n = L->nnz;
+    const int n_out = (int)L->cfg.n_out;
+    if (removed) *removed = 0;
+    if (n == 0) return SL_OK;
+    int rc = topo_sync_csr_vel(L, s);
+    if (rc) return rc;
+    float *imp = at<float>(L, L->cp.f0);
+    uint32_t *keep = at<uint32_t>(L, L->cp.keep), *kscan = at<uint32_t>(L, L->cp.kscan);
+    int *s_col = at<int>(L, L->cp.s_col), *rowptr_s = at<int>(L, L->cp.rowptr_s);
+    float *s_val = at<float>(L, L->cp.s_val), *s_vel = at<float>(L, L->cp.s_vel);
+    rc = topo_importance(L, imp, s);
+    if (rc) return rc;
+    hipLaunchKernelGGL(importance_keep_kernel, dim3(nblk(n + 1)), dim3(TB), 0, s, n, n_out, L->rowptr, imp, threshold, keep);
+    SL_HIP(L, scan_excl<uint32_t>(at<char>(L, L->cp.temp), L->cp.temp_bytes, keep, kscan, (size_t)n + 1, s));
+    uint32_t kept = 0;
+    rc = read_back(L, &kept, kscan + n, sizeof(uint32_t), s);
+    if (rc) return rc;
+    if ((long)kept == n) return SL_OK;
+    hipLaunchKernelGGL(compact_kernel, dim3(nblk(n)), dim3(TB), 0, s, n, keep, kscan, L->colidx, L->val, L->vel, s_col,
+                       s_val, s_vel);
+    hipLaunchKernelGGL(survivor_rowptr_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, n_out, L->rowptr, kscan, rowptr_s);
+    hipLaunchKernelGGL(copy_back_kernel, dim3(nblk(kept)), dim3(TB), 0, s, (long)kept, s_col, s_val, s_vel, L->colidx,
+                       L->val, L->vel);
+    SL_HIP(L, hipMemcpyAsync(L->rowptr, rowptr_s, sizeof(int) * ((size_t)n_out + 1), hipMemcpyDeviceToDevice, s));
+    SL_HIP(L, hipGetLastError());
+    L->nnz = kept;
+    if (removed) *removed = n - (long)kept;
     return topo_finalize(L, s);
 }
 

@@ -393,3 +393,61 @@ def test_linked_backward_equals_unlinked(gpu, oracle, dims, nnz, B, max_batch):
         assert np.array_equal(g_u.view(np.uint32), g_l.view(np.uint32))
         assert np.array_equal(gb_u.view(np.uint32), gb_l.view(np.uint32))
     assert np.abs(results[0][0][0]).max() > 0
+
+
+# ------------------------------------------------------------------------------------------ Importance Pruning
+@pytest.mark.parametrize("n_in,n_out,nnz,need_gx", [(500, 400, 9000, True), (500, 400, 9000, False),
+                                                     (40, 30, 1000, True),          # dense sampler mode before pruning
+                                                     (100000, 70000, 1700000, True)])
+def test_importance_pruning_bit_exact(gpu, oracle, n_in, n_out, nnz, need_gx):
+    import torch
+    G, O = make_pair(gpu, oracle, n_in, n_out, nnz, need_input_grad=need_gx, seed=41)
+    rng = np.random.default_rng(nnz + 1)
+    rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+    val = (rng.standard_normal(nnz) * 0.1).astype(np.float32)
+    vel = (rng.standard_normal(nnz) * 0.01).astype(np.float32)
+    G.import_csr(rowptr, colidx, val, vel, bias, bias_vel)
+    O.set_state(rowptr, colidx, val, vel, bias, bias_vel)
+    imp = G.importance()
+    assert np.array_equal(imp.view(np.uint32), O.importance_f32().view(np.uint32))      # eq. (4), same fp32 order
+    t = float(np.quantile(imp.astype(np.float64), 0.3))
+    removed = G.importance_prune(t)
+    assert removed == O.importance_prune(t) and removed > 0
+    assert G.nnz == O.nnz == nnz - removed
+    assert_same_topology(G, O)
+    # the pruned layer still trains: one forward/backward/update against the oracle
+    B = 64
+    x = rng.standard_normal((n_in, B)).astype(np.float32)
+    ga = rng.standard_normal((n_out, B)).astype(np.float32)
+    a_ref = O.forward(x)
+    gx_ref = O.backward(x, ga, need_input_grad=need_gx)
+    ad = torch.zeros((n_out, B), device="cuda")
+    gxd = torch.zeros((n_in, B), device="cuda") if need_gx else None
+    xd = dev(torch, x)
+    G.forward(xd, B, ad)
+    G.backward(xd, dev(torch, ga), B, gxd)
+    close(ad.cpu().numpy(), a_ref, 1e-4, "a after pruning")
+    g, gb = G.export_grad()
+    keep_rows = np.abs(O.z).min(axis=1) > 1e-5                     # rows away from the kink of eq. (3)
+    rows = np.repeat(np.arange(n_out), np.diff(O.rowptr))
+    close(g[keep_rows[rows]], O.grad_val[keep_rows[rows]], 1e-4, "grad_val after pruning")
+    G.update()
+    # and it still evolves: from identical bits, with the reduced nnz preserved
+    rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+    O.set_state(O.rowptr, O.colidx, O.val, O.vel, O.bias, O.bias_vel)
+    G.import_csr(O.rowptr, O.colidx, O.val, O.vel, O.bias, O.bias_vel)
+    for gen in (1, 2):
+        O.evolve(0.3, gen)
+        G.evolve(0.3, gen)
+        assert G.nnz == nnz - removed
+        assert_same_topology(G, O)
+    # pruning everything leaves an empty but usable layer
+    assert G.importance_prune(1e30) == nnz - removed and G.nnz == 0
+    G.forward(xd, B, ad)
+    assert np.array_equal(ad.cpu().numpy(), gpu_bias_act(O.bias, O, B))     # a = f(bias): no connection is left
+    G.close()
+
+
+def gpu_bias_act(bias, O, B):
+    z = np.repeat(np.asarray(bias, np.float32)[:, None], B, axis=1)
+    return np.where(z > 0, z, (-O.alpha if O.act_parity == 0 else O.alpha) * z).astype(np.float32)

@@ -391,3 +391,39 @@ def test_workload_tables_match_the_configurations():
     blocks = wl.to_batch_blocks(x[:200], 128)
     assert blocks.shape == (2, 500, 128) and np.array_equal(blocks[1, :, :72], x[128:200].T)
     assert np.all(blocks[1, :, 72:] == 0)
+
+
+# ---------------------------------------------------------------------------- Importance Pruning, eq. (4) + Algorithm 2
+def test_importance_pruning_removes_exactly_the_weak_neurons(oracle):
+    L = make_layer(oracle, 60, 50, 900, seed=23)
+    rng = np.random.default_rng(6)
+    L.vel = rng.standard_normal(900).astype(np.float32)
+    dense_before = L.dense()
+    imp64 = np.abs(dense_before).sum(axis=1)
+    imp = L.importance_f32()
+    assert np.allclose(imp, imp64, rtol=1e-6) and np.allclose(L.importance(), imp64, rtol=1e-6)
+    t = float(np.sort(imp64)[20]) * (1 - 1e-4) + float(np.sort(imp64)[19]) * 1e-4   # strictly between two neurons
+    weak = imp64 < t
+    assert weak.sum() == 20
+    flat0, val0, vel0 = L.flat().copy(), L.val.copy(), L.vel.copy()
+    rows0 = (flat0 // np.uint64(60)).astype(np.int64)
+    removed = L.importance_prune(t)
+    assert removed == int(np.diff(np.r_[0, np.cumsum(np.bincount(rows0, minlength=50))])[weak].sum())
+    assert L.nnz == 900 - removed and L.rowptr[-1] == L.nnz
+    assert np.all(np.diff(L.rowptr)[weak] == 0)                          # weak neurons lose every incoming connection
+    keep = ~weak[rows0]
+    assert np.array_equal(L.flat(), flat0[keep])                         # the others are untouched, bit for bit
+    assert np.array_equal(L.val.view(np.uint32), val0[keep].view(np.uint32))
+    assert np.array_equal(L.vel.view(np.uint32), vel0[keep].view(np.uint32))
+    d = L.dense()
+    assert np.all(d[weak] == 0) and np.array_equal(d[~weak], dense_before[~weak])
+    # threshold 0 removes nothing (importances are sums of magnitudes), a huge threshold everything
+    assert L.importance_prune(0.0) == 0
+    n_before = L.nnz
+    assert L.importance_prune(1e30) == n_before and L.nnz == 0 and not L.rowptr.any()
+    # SET evolution afterwards preserves the reduced count
+    L2 = make_layer(oracle, 60, 50, 900, seed=23)
+    L2.importance_prune(t)
+    n2 = L2.nnz
+    L2.evolve(0.3, 1)
+    assert L2.nnz == n2
