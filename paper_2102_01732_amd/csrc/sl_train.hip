@@ -11,7 +11,6 @@
 // outstanding per group; the work is HBM-bound (0.5 flop/byte), so there is no MFMA here.
 #include <stdarg.h>
 #include <stdio.h>
-#include <stdlib.h>
 
 #include <type_traits>
 
@@ -447,7 +446,6 @@ __global__ __launch_bounds__(BLOCK) void softmax_ce_kernel(const float *z, long 
 static int group_width(int B) { return B <= 32 ? 8 : B <= 64 ? 16 : B <= 128 ? 32 : 64; }
 static int chunk_width(const SegMat &m, long nnz)
 {
-    if (const char *f = getenv("SL_FORCE_U")) return atoi(f);
     const double mean = m.nv > 0 ? (double)nnz / (double)m.nv : 0.0;
     return mean <= 2.5 ? 2 : mean <= 6.0 ? 4 : 8;
 }

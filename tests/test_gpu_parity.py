@@ -451,3 +451,85 @@ def test_importance_pruning_bit_exact(gpu, oracle, n_in, n_out, nnz, need_gx):
 def gpu_bias_act(bias, O, B):
     z = np.repeat(np.asarray(bias, np.float32)[:, None], B, axis=1)
     return np.where(z > 0, z, (-O.alpha if O.act_parity == 0 else O.alpha) * z).astype(np.float32)
+
+
+# ------------------------------------------------------------------------------------------ sweep-sized layer
+def test_sweep_sized_layer_two_batch_tiles(gpu, oracle):
+    """One 262 144 x 262 144 layer (epsilon = 4) at B = 512: two batch tiles of 256 columns, chunk
+    width 8, the launch shapes of the single-layer sweep; every output compared with the oracle."""
+    import torch
+    n, B = wl.SWEEP_N, 512
+    spec = wl.sweep_layer(4)
+    G, O = make_pair(gpu, oracle, n, n, spec.nnz, limit=spec.init_limit, max_batch=B, seed=wl.DEFAULT_SEED, layer_id=0)
+    assert_same_topology(G, O)
+    x = wl.dense_operand(n, B, 5)
+    ga = wl.dense_operand(n, B, 6)
+    a_ref = O.forward(x)
+    gx_ref = O.backward(x, ga)
+    xd, gad = dev(torch, x), dev(torch, ga)
+    ad, gxd = torch.empty_like(xd), torch.empty_like(xd)
+    G.forward(xd, B, ad)
+    G.backward(xd, gad, B, gxd)
+    g, gb = G.export_grad()
+    close(ad.cpu().numpy(), a_ref, 1e-4, "a")
+    # rows whose pre-activation sits on the kink of eq. (3) may take the other branch: leave them out
+    safe = np.abs(O.z).min(axis=1) > 1e-5
+    rows = np.repeat(np.arange(n), np.diff(O.rowptr))
+    assert safe.mean() > 0.95
+    close(g[safe[rows]], O.grad_val[safe[rows]], 1e-4, "grad_val")
+    close(gb[safe], O.grad_bias[safe], 1e-4, "grad_bias")
+    # an input gradient row is exact unless one of the rows it gathers is unsafe
+    touched = np.zeros(n, bool)
+    touched[O.colidx[~safe[rows]]] = True
+    close(gxd.cpu().numpy()[~touched], gx_ref[~touched], 1e-4, "grad_x")
+    G.close()
+
+
+# ------------------------------------------------------------------------------------------ error paths on a live layer
+def test_argument_and_call_order_errors(gpu):
+    import torch
+    cfg = gpu.make_config(64, 48, nnz=500, init_limit=0.1, max_batch=32, need_input_grad=True)
+    L = gpu.SparseLayer(cfg)
+    x = torch.zeros((64, 32), device="cuda")
+    a = torch.zeros((48, 32), device="cuda")
+    gx = torch.zeros((64, 32), device="cuda")
+
+    def code(f):
+        with pytest.raises(gpu.SparseSetError) as e:
+            f()
+        return e.value.code
+
+    assert code(lambda: L.backward(x, a, 32, gx)) == gpu.SL_ESTATE          # backward before forward
+    assert code(L.update) == gpu.SL_ESTATE                                  # update before backward
+    assert code(lambda: L.forward(x, 33, a)) == gpu.SL_EINVAL               # B > max_batch
+    assert code(lambda: L.forward(x, 0, a)) == gpu.SL_EINVAL
+    assert code(lambda: L.forward(torch.zeros((64, 28), device="cuda"), 32, a)) == gpu.SL_EINVAL   # ld < B
+    assert code(lambda: L.forward(x[:, 1:], 28, a)) == gpu.SL_EINVAL        # misaligned base pointer
+    L.forward(x, 32, a)
+    assert code(lambda: L.backward(x, a, 16, gx)) == gpu.SL_ESTATE          # other B than forward
+    assert code(lambda: L.backward(x, a, 32, None)) == gpu.SL_EINVAL        # grad_x missing, no producer linked
+    assert code(lambda: L.backward(x, None, 32, gx)) == gpu.SL_EINVAL       # grad_a missing, nothing handed over
+    assert code(L.export_grad) == gpu.SL_ESTATE
+    L.backward(x, a, 32, gx)
+    L.export_grad()
+    L.update()
+    assert code(lambda: L.evolve(1.5, 1)) == gpu.SL_EINVAL
+    assert code(lambda: L.evolve(0.3, 0)) == gpu.SL_EINVAL
+    rowptr, colidx, val, vel, bias, bias_vel = L.export_csr()
+    bad = colidx.copy()
+    bad[0] = 64
+    assert code(lambda: L.import_csr(rowptr, bad, val)) == gpu.SL_EINVAL
+    assert code(lambda: L.import_csr(rowptr[::-1].copy(), colidx, val)) == gpu.SL_EINVAL
+    other = gpu.SparseLayer(gpu.make_config(10, 64, nnz=50, init_limit=0.1, max_batch=16, need_input_grad=False))
+    assert code(lambda: L.link_producer(other)) == gpu.SL_EINVAL            # producer's max_batch too small
+    assert "max_batch" in gpu.lib().sparse_layer_last_error(L.handle).decode()
+    # a state buffer that is too small is refused at init
+    import ctypes as C
+    sb, cb = gpu.query_sizes(cfg)
+    st = torch.empty(sb // 2, dtype=torch.uint8, device="cuda")
+    sc = torch.empty(cb + 256, dtype=torch.uint8, device="cuda")
+    h = C.c_void_p(None)
+    assert gpu.lib().sparse_layer_init(C.byref(cfg), st.data_ptr(), st.numel(), sc.data_ptr(), sc.numel(), None,
+                                       C.byref(h)) == gpu.SL_ENOMEM
+    L.close()
+    other.close()
