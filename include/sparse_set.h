@@ -86,6 +86,12 @@ int sparse_layer_init(const sl_config *cfg, void *state_dev, size_t state_bytes,
 int sparse_layer_forward(sl_layer *layer, const float *x_dev, int64_t ldx, int32_t B, float *a_dev,
                          int64_t lda, void *hip_stream);
 
+/* Forward only (the paper's test-set evaluation, its "inference bottleneck" at extreme size): the same
+ * computation as sparse_layer_forward, but nothing is saved for a backward pass and the layer's
+ * training state is untouched, so it may be called between forward and backward.  Asynchronous. */
+int sparse_layer_infer(sl_layer *layer, const float *x_dev, int64_t ldx, int32_t B, float *a_dev, int64_t lda,
+                       void *hip_stream);
+
 /* Backward of the same minibatch (must follow forward with the same B):
  *   dz = grad_a * f_l'(z)                     (f' at z = 0 is the "z <= 0" branch of eq. 3)
  *   grad_bias[j] = sum_b dz[j][b]

@@ -26,6 +26,7 @@ EXPORTS = [
     "sparse_layer_nnz", "sparse_layer_export_csr", "sparse_layer_import_csr", "sparse_layer_export_grad",
     "sparse_layer_set_lr", "sparse_layer_last_error", "sparse_layer_profile_begin", "sparse_layer_profile_end",
     "sparse_kernel_name", "sparse_layer_link_producer", "sparse_layer_importance", "sparse_layer_importance_prune",
+    "sparse_layer_infer",
 ]
 N_KERNEL_IDS = 7
 
@@ -56,6 +57,7 @@ def lib():
         L.sparse_layer_query_sizes.argtypes = [C.POINTER(SlConfig), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         L.sparse_layer_init.argtypes = [C.POINTER(SlConfig), vp, C.c_size_t, vp, C.c_size_t, vp, C.POINTER(vp)]
         L.sparse_layer_forward.argtypes = [vp, f32p, i64, i32, f32p, i64, vp]
+        L.sparse_layer_infer.argtypes = [vp, f32p, i64, i32, f32p, i64, vp]
         L.sparse_layer_backward.argtypes = [vp, f32p, i64, f32p, i64, i32, f32p, i64, vp]
         L.sparse_layer_update.argtypes = [vp, vp]
         L.sparse_layer_evolve.argtypes = [vp, C.c_double, C.c_uint64, vp]
@@ -135,6 +137,10 @@ class SparseLayer:
     def forward(self, x: torch.Tensor, B: int, a: torch.Tensor):
         self._check(lib().sparse_layer_forward(self.handle, x.data_ptr(), x.stride(0), B, a.data_ptr(), a.stride(0),
                                                _stream()), "sparse_layer_forward")
+
+    def infer(self, x: torch.Tensor, B: int, a: torch.Tensor):
+        self._check(lib().sparse_layer_infer(self.handle, x.data_ptr(), x.stride(0), B, a.data_ptr(), a.stride(0),
+                                             _stream()), "sparse_layer_infer")
 
     def link_producer(self, producer: Optional["SparseLayer"]):
         self._check(lib().sparse_layer_link_producer(self.handle, producer.handle if producer else None),
@@ -257,6 +263,14 @@ class SparseMLP:
         cur = x
         for layer, a in zip(self.layers, self.acts):
             layer.forward(cur, B, a)
+            cur = a
+        return cur
+
+    def infer(self, x: torch.Tensor, B: int, outs: Sequence[torch.Tensor]) -> torch.Tensor:
+        """Forward only, into caller-provided activation buffers (B may differ from training)."""
+        cur = x
+        for layer, a in zip(self.layers, outs):
+            layer.infer(cur, B, a)
             cur = a
         return cur
 

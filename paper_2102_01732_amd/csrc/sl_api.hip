@@ -262,12 +262,25 @@ int sparse_layer_forward(sl_layer *L, const float *x_dev, int64_t ldx, int32_t B
     rc = check_dense(L, a_dev, lda, B, "a");
     if (rc) return rc;
     L->last_stream = (hipStream_t)hip_stream;
-    rc = launch_forward(L, x_dev, ldx, B, a_dev, lda, L->last_stream);
+    rc = launch_forward(L, x_dev, ldx, B, a_dev, lda, true, L->last_stream);
     if (rc) return rc;
     L->phase = 1;
     L->last_B = B;
     L->dz_ready = 0;
     return SL_OK;
+}
+
+int sparse_layer_infer(sl_layer *L, const float *x_dev, int64_t ldx, int32_t B, float *a_dev, int64_t lda,
+                       void *hip_stream)
+{
+    if (!L) return SL_EINVAL;
+    if (B <= 0 || B > L->cfg.max_batch) return set_err(L, SL_EINVAL, "B = %d outside 1..max_batch = %d", B, L->cfg.max_batch);
+    int rc = check_dense(L, x_dev, ldx, B, "x");
+    if (rc) return rc;
+    rc = check_dense(L, a_dev, lda, B, "a");
+    if (rc) return rc;
+    L->last_stream = (hipStream_t)hip_stream;
+    return launch_forward(L, x_dev, ldx, B, a_dev, lda, false, L->last_stream);
 }
 
 int sparse_layer_link_producer(sl_layer *L, sl_layer *producer)

@@ -129,7 +129,7 @@ int64_t sampler_window(double M, double n_occ, double k);
 int choose_seg(int64_t n_rows, int64_t nnz);
 
 // training kernels (sl_train.hip)
-int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, int64_t lda, hipStream_t s);
+int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, int64_t lda, bool save_sign, hipStream_t s);
 int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, int64_t ldg, int B, float *gx,
                     int64_t ldgx, hipStream_t s);
 int launch_update(sl_layer *L, hipStream_t s);

@@ -81,7 +81,7 @@ __device__ __forceinline__ void finish(const Epi &e, long row, int c, bool activ
         float4 r = z;
         if (e.act_kind != 0) {
             const unsigned nib = (z.x > 0.f ? 1u : 0u) | (z.y > 0.f ? 2u : 0u) | (z.z > 0.f ? 4u : 0u) | (z.w > 0.f ? 8u : 0u);
-            e.mask_w[row * e.ldm + (c >> 2)] = (uint8_t)nib;
+            if (e.mask_w) e.mask_w[row * e.ldm + (c >> 2)] = (uint8_t)nib;
             r.x = z.x > 0.f ? z.x : e.slope * z.x;
             r.y = z.y > 0.f ? z.y : e.slope * z.y;
             r.z = z.z > 0.f ? z.z : e.slope * z.z;
@@ -502,7 +502,7 @@ static void launch_fix(sl_layer *L, const SegMat &m, const Epi &epi, int G, int 
     });
 }
 
-int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, int64_t lda, hipStream_t s)
+int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, int64_t lda, bool save_sign, hipStream_t s)
 {
     const SegMat &m = L->fwd;
     const int G = group_width(B), U = chunk_width(m, L->nnz);
@@ -511,7 +511,7 @@ int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, in
     f.vptr = m.vptr; f.v2row = m.v2row; f.nv = m.nv; f.idx = m.idx; f.w = L->val; f.x = x; f.ldx = ldx;
     f.part = m.split ? (float *)(L->scratch + L->cp.partial) : nullptr; f.ldp = L->ldz;
     Epi &e = f.epi;
-    e.mode = EPI_FWD; e.out = a; e.ldo = lda; e.bias = L->bias; e.mask_w = L->mask; e.mask_r = nullptr; e.ldm = L->ldm;
+    e.mode = EPI_FWD; e.out = a; e.ldo = lda; e.bias = L->bias; e.mask_w = save_sign ? L->mask : nullptr; e.mask_r = nullptr; e.ldm = L->ldm;
     e.gb = nullptr; e.act_kind = L->cfg.act_kind; e.slope = L->cfg.act_parity == 0 ? -L->cfg.alpha : L->cfg.alpha; e.B = B;
     {
         ProfScope ps(L, K_FWD, s);

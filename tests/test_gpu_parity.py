@@ -533,3 +533,67 @@ def test_argument_and_call_order_errors(gpu):
                                        C.byref(h)) == gpu.SL_ENOMEM
     L.close()
     other.close()
+
+
+# ------------------------------------------------------------------------------------------ inference, weight decay
+def test_infer_equals_forward_and_leaves_training_state_alone(gpu, oracle):
+    import torch
+    G, O = make_pair(gpu, oracle, 300, 700, 6000, max_batch=512, limit=0.2)
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((300, 128)).astype(np.float32)
+    ga = rng.standard_normal((700, 128)).astype(np.float32)
+    xd = dev(torch, x)
+    a_train = torch.zeros((700, 128), device="cuda")
+    G.forward(xd, 128, a_train)
+    # a larger inference batch in between must not disturb the saved signs of the training batch
+    xbig = dev(torch, rng.standard_normal((300, 512)).astype(np.float32))
+    a_big = torch.zeros((700, 512), device="cuda")
+    G.infer(xbig, 512, a_big)
+    close(a_big.cpu().numpy(), O.forward(xbig.cpu().numpy()), 1e-4, "inference output")
+    a_inf = torch.zeros((700, 128), device="cuda")
+    G.infer(xd, 128, a_inf)
+    assert torch.equal(a_inf, a_train)
+    gx = torch.zeros((300, 128), device="cuda")
+    G.backward(xd, dev(torch, ga), 128, gx)
+    O.forward(x)
+    gx_ref = O.backward(x, ga)
+    g, gb = G.export_grad()
+    safe = np.abs(O.z).min(axis=1) > 1e-5
+    rows = np.repeat(np.arange(700), np.diff(O.rowptr))
+    close(g[safe[rows]], O.grad_val[safe[rows]], 1e-4, "grad_val")
+    G.close()
+
+
+def test_weight_decay_term_of_the_update(gpu, oracle):
+    import torch
+    lam = 0.05
+    cfg = gpu.make_config(200, 150, nnz=3000, act_kind=1, act_parity=1, alpha=0.6, init_limit=0.3, lr=0.01, momentum=0.9,
+                          weight_decay=lam, seed=4, layer_id=1, max_batch=64, need_input_grad=True)
+    G = gpu.SparseLayer(cfg)
+    O = oracle.OracleLayer(200, 150, 3000, 1, 1, 0.6, 0.3, 0.01, 0.9, lam, 4, 1)
+    assert_same_topology(G, O)
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((200, 64)).astype(np.float32)
+    ga = rng.standard_normal((150, 64)).astype(np.float32)
+    xd = dev(torch, x)
+    a = torch.zeros((150, 64), device="cuda")
+    gx = torch.zeros((200, 64), device="cuda")
+    for _ in range(3):
+        O.forward(x)
+        O.backward(x, ga)
+        G.forward(xd, 64, a)
+        G.backward(xd, dev(torch, ga), 64, gx)
+        g, gb = G.export_grad()
+        O.grad_val, O.grad_bias = g.copy(), gb.copy()     # same gradient in: the update must agree bit for bit
+        rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+        O.set_state(rowptr, colidx, val, vel, bias, bias_vel)
+        O.grad_val, O.grad_bias = g.copy(), gb.copy()
+        O.update()
+        G.update()
+        _, _, val2, vel2, bias2, _ = G.export_csr()
+        assert np.array_equal(val2.view(np.uint32), O.val.view(np.uint32))
+        assert np.array_equal(vel2.view(np.uint32), O.vel.view(np.uint32))
+        assert np.array_equal(bias2.view(np.uint32), O.bias.view(np.uint32))
+    # the decay really acts: with zero gradient the weights shrink by lr*lambda*w per step (plus momentum)
+    assert lam > 0 and not np.array_equal(val2, val)
+    G.close()
