@@ -417,16 +417,22 @@ __global__ void vcount_kernel(int n_rows, const int *ptr, int seg, uint32_t *cnt
     }
     cnt[r] = c;
 }
-__global__ void vfill_kernel(int n_rows, const int *ptr, int seg, const int *rvptr, int *vptr, int *v2row, int nnz)
+// one thread per virtual row: its row is the last r with rvptr[r] <= v
+__global__ void vfill_kernel(int n_rows, const int *ptr, int seg, const int *rvptr, int *vptr, int *v2row, int nnz, int nv)
+{
+    const int v = blockIdx.x * TB + threadIdx.x;
+    if (v > nv) return;
+    if (v == nv) { vptr[nv] = nnz; return; }
+    const int r = row_of(rvptr, n_rows, v);
+    vptr[v] = ptr[r] + (v - rvptr[r]) * seg;
+    v2row[v] = r;
+}
+// one thread per row writes the row index of each of its entries (rows are short where this is used)
+__global__ void expand_rows_kernel(int n_rows, const int *ptr, int *rowid)
 {
     const int r = blockIdx.x * TB + threadIdx.x;
-    if (r > n_rows) return;
-    if (r == n_rows) { vptr[rvptr[n_rows]] = nnz; return; }
-    const int v0 = rvptr[r], v1 = rvptr[r + 1];
-    for (int v = v0; v < v1; ++v) {
-        vptr[v] = ptr[r] + (v - v0) * seg;
-        v2row[v] = r;
-    }
+    if (r >= n_rows) return;
+    for (int p = ptr[r]; p < ptr[r + 1]; ++p) rowid[p] = r;
 }
 __global__ void iota_copy_kernel(long n, const int *col, uint32_t *key, uint32_t *pay)
 {
@@ -446,14 +452,14 @@ __global__ void colptr_kernel(int n_cols, const uint32_t *key_sorted, long n, in
     }
     colptr[c] = (int)lo;
 }
-__global__ void csc_fill_kernel(long n, int n_rows, const int *rowptr, const uint32_t *pos_sorted, const float *val,
-                                const float *vel, int *rowidx, int *csr_pos, float *valT, float *velT)
+__global__ void csc_fill_kernel(long n, int n_rows, const int *rowptr, const int *rowid, const uint32_t *pos_sorted,
+                                const float *val, const float *vel, int *rowidx, int *csr_pos, float *valT, float *velT)
 {
     const long q = (long)blockIdx.x * TB + threadIdx.x;
     if (q >= n) return;
     const int p = (int)pos_sorted[q];
     csr_pos[q] = p;
-    rowidx[q] = row_of(rowptr, n_rows, p);
+    rowidx[q] = rowid ? rowid[p] : row_of(rowptr, n_rows, p);
     valT[q] = val[p];
     velT[q] = vel[p];
 }
@@ -547,8 +553,8 @@ static int build_vrows(sl_layer *L, SegMat &m, int nnz, hipStream_t s)
     rc = read_back(L, &nv, m.rvptr_store + m.n_rows, sizeof(int), s);
     if (rc) return rc;
     if (nv > m.nv_cap) return set_err(L, SL_ENOMEM, "virtual rows %d exceed capacity %d", nv, m.nv_cap);
-    hipLaunchKernelGGL(vfill_kernel, dim3(nblk(m.n_rows + 1)), dim3(TB), 0, s, m.n_rows, m.ptr, m.seg, m.rvptr_store,
-                       m.vptr_store, m.v2row_store, nnz);
+    hipLaunchKernelGGL(vfill_kernel, dim3(nblk(nv + 1)), dim3(TB), 0, s, m.n_rows, m.ptr, m.seg, m.rvptr_store,
+                       m.vptr_store, m.v2row_store, nnz, nv);
     m.split = 1; m.vptr = m.vptr_store; m.v2row = m.v2row_store; m.rvptr = m.rvptr_store; m.nv = nv;
     SL_HIP(L, hipGetLastError());
     return SL_OK;
@@ -569,7 +575,13 @@ int topo_finalize(sl_layer *L, hipStream_t s)
         hipLaunchKernelGGL(iota_copy_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, L->colidx, kA, vA);
         SL_HIP(L, sort_pairs<uint32_t>(at<char>(L, L->cp.temp), L->cp.temp_bytes, kA, kB, vA, vB, (size_t)n,
                                        bit_length((uint64_t)n_in - 1), &ks, &vs, s));
-        hipLaunchKernelGGL(csc_fill_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, n_out, L->rowptr, vs, L->val,
+        // row index of every CSR slot: expanded once per row when rows are short, else found by search
+        int *rowid = nullptr;
+        if (!L->fwd.split) {
+            rowid = (int *)(vs == vA ? vB : vA);   // the payload buffer the sort left free
+            hipLaunchKernelGGL(expand_rows_kernel, dim3(nblk(n_out)), dim3(TB), 0, s, n_out, L->rowptr, rowid);
+        }
+        hipLaunchKernelGGL(csc_fill_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, n_out, L->rowptr, rowid, vs, L->val,
                            L->vel, L->rowidx, L->csr_pos, L->valT, L->velT);
     }
     hipLaunchKernelGGL(colptr_kernel, dim3(nblk(n_in + 1)), dim3(TB), 0, s, n_in, ks, (long)n, L->colptr);

@@ -346,6 +346,11 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
                 cc[u] = a.idx[q];
                 if (SPMM) ww[u] = (p + u < p1) ? a.w[q] : 0.f;
             }
+            // later batch tiles add to what the earlier ones stored; fetch it with the indices, not after
+            // the reduction, so that its latency hides behind the row gathers
+            const bool writer = lane < U && p + lane < p1;
+            float g_prev = 0.f;
+            if (tile > 0 && writer) g_prev = a.g[p + lane];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 xv[u] = zero4();
@@ -365,10 +370,7 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
                 s[u] = fmaf(h.x, xv[u].x, fmaf(h.y, xv[u].y, fmaf(h.z, xv[u].z, h.w * xv[u].w)));
             }
             const float r = reduce_chunk<G, U>(s, lane);
-            if (lane < U && p + lane < p1) {
-                if (tile == 0) a.g[p + lane] = r;
-                else a.g[p + lane] += r;
-            }
+            if (writer) a.g[p + lane] = g_prev + r;
         }
         if (SPMM) {
             if (a.part) {
