@@ -226,6 +226,23 @@ def main():
                    sample=f"one training step (forward, loss, backward, update) on the first {ns} samples of "
                           f"minibatch 0 at the full layer shapes; {c1 - c0:.1f} s; evolution not included")
 
+    # ---- sparse averaging of two replicas (eq. 2 + magnitude re-pruning) of the first 10^6 x 10^6 layer
+    average = None
+    if len(net.layers) > 1:
+        spec1 = w.layers[1]
+        twin = binding.SparseLayer(binding.make_config(
+            spec1.n_in, spec1.n_out, nnz=spec1.nnz, act_kind=spec1.act_kind, act_parity=spec1.act_parity, alpha=w.alpha,
+            init_limit=spec1.init_limit, lr=w.lr, momentum=w.momentum, seed=w.seed + 1, layer_id=spec1.layer_id,
+            max_batch=B, need_input_grad=True), scratch=net.scratch)
+        torch.cuda.synchronize()
+        ta0 = time.perf_counter()
+        binding.average_layers(twin, [twin, net.layers[1]])
+        torch.cuda.synchronize()
+        average = dict(layer=1, replicas=2, ms=(time.perf_counter() - ta0) * 1e3, nnz_after=twin.nnz)
+        twin.close()
+        del twin
+        torch.cuda.empty_cache()
+
     # ---- Importance Pruning (eq. 4 + Algorithm 2) on the first 10^6 x 10^6 layer: weakest 10 % of the neurons
     L1 = net.layers[1] if len(net.layers) > 1 else net.layers[0]
     torch.cuda.synchronize()
@@ -254,7 +271,7 @@ def main():
                            nnz=[s.nnz for s in w.layers], alpha=w.alpha, zeta=w.zeta,
                            evolutions_in_timed_region=K // n_blocks, parallelism="single GPU"),
                roofline=roofline, cpu_baseline=cpu, evolve_ms_all_layers=evolve_ms, kernels=kernels[:12],
-               importance_pruning=importance, other_workloads=others)
+               importance_pruning=importance, sparse_average=average, other_workloads=others)
     print(json.dumps(out))
 
 

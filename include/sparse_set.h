@@ -134,6 +134,19 @@ int sparse_layer_importance(sl_layer *layer, float *importance_host);
  * NULL) receives the number of removed connections.  Synchronises the stream. */
 int sparse_layer_importance_prune(sl_layer *layer, float threshold, int64_t *removed, void *hip_stream);
 
+/* Sparse model averaging, eq. (2) and the last step of Algorithm 1 ("produce averaged model and
+ * select a fraction S of weights with bigger magnitude"): dst <- (1/K) * sum of the K replicas, where
+ * a connection that a replica does not have counts as zero; the union of the patterns is then
+ * pruned by magnitude (ordering key as in sparse_layer_evolve) back to dst's current number of
+ * connections.  Each value is the fp32 sum in replica order divided by K.  Biases are averaged the
+ * same way; all velocities of dst become zero.  dst may be one of the replicas; the replicas must
+ * have dst's shape and at most dst's capacity (its nnz at creation) results.  1 <= K <= 16.
+ * scratch_dev: device buffer of sparse_layers_average_query(sum of the replicas' nnz) bytes,
+ * 256-byte aligned, used only during the call.  Synchronises the stream. */
+int sparse_layers_average_query(int64_t total_entries, size_t *scratch_bytes);
+int sparse_layers_average(sl_layer *dst, sl_layer *const *replicas, int32_t K, void *scratch_dev,
+                          size_t scratch_bytes, void *hip_stream);
+
 int sparse_layer_destroy(sl_layer *layer);
 
 /* Softmax + cross-entropy over C output neurons (the loss is unnamed in the paper).

@@ -76,6 +76,10 @@ def lib():
         L.or_importance.restype = None
         L.or_importance_f32.argtypes = [c.c_int64, _i32p, _f32p, _f32p]
         L.or_importance_f32.restype = None
+        L.or_average_sorted.argtypes = [c.c_int64, _u64p, _f32p, c.c_int32, _u64p, _f32p]
+        L.or_average_sorted.restype = c.c_int64
+        L.or_keep_largest.argtypes = [c.c_int64, _f32p, _u64p, c.c_int64, _u8p]
+        L.or_keep_largest.restype = c.c_int64
         _lib = L
     return _lib
 
@@ -285,6 +289,37 @@ class OracleLayer:
         rows = np.repeat(np.arange(self.n_out), np.diff(self.rowptr))
         W[rows, self.colidx] = self.val
         return W
+
+
+def average_layers(dst: OracleLayer, replicas: Sequence[OracleLayer]) -> int:
+    """Last step of Algorithm 1: dst <- average of the K replicas (eq. 2; a connection missing from a
+    replica counts as zero), re-pruned by magnitude to dst's current number of connections; biases
+    are averaged, velocities reset.  Returns the size of the union of the patterns."""
+    K = len(replicas)
+    n_keep = dst.nnz
+    flat = np.concatenate([r.flat() for r in replicas])
+    val = np.concatenate([r.val for r in replicas]).astype(np.float32)
+    order = np.argsort(flat, kind="stable")                  # equal positions stay in replica order
+    T = flat.size
+    uflat = np.zeros(max(T, 1), np.uint64)
+    uval = np.zeros(max(T, 1), np.float32)
+    U = lib().or_average_sorted(T, np.ascontiguousarray(flat[order]) if T else np.zeros(1, np.uint64),
+                                np.ascontiguousarray(val[order]) if T else np.zeros(1, np.float32), K, uflat, uval)
+    uflat, uval = uflat[:U].copy(), uval[:U].copy()
+    remove = np.zeros(max(U, 1), np.uint8)
+    rc = lib().or_keep_largest(U, uval if U else np.zeros(1, np.float32), uflat if U else np.zeros(1, np.uint64),
+                               n_keep, remove)
+    if rc < 0:
+        raise MemoryError("or_keep_largest")
+    keep = ~remove[:U].astype(bool)
+    bias = replicas[0].bias.copy()
+    for r in replicas[1:]:
+        bias = (bias + r.bias).astype(np.float32)
+    bias = (bias / np.float32(K)).astype(np.float32)
+    rowptr, colidx = csr_from_flat(uflat[keep], dst.n_in, dst.n_out)
+    dst.set_state(rowptr, colidx, uval[keep], np.zeros(int(keep.sum()), np.float32), bias,
+                  np.zeros(dst.n_out, np.float32))
+    return int(U)
 
 
 # ----------------------------------------------------------------------------------------------

@@ -32,6 +32,8 @@
  *   or_prune_select       Algorithm 2's removal step (magnitude based).
  *   or_softmax_ce         softmax + cross-entropy loss and its gradient (loss unnamed in the
  *                         paper; this is the reading used throughout).
+ *   or_average_sorted,    sparse averaging of K replicas, eq. (2), and the magnitude re-pruning that
+ *   or_keep_largest       follows it (WASAP-SGD phase 2, last step of Algorithm 1).
  *   or_importance(_f32)   neuron importance, eq. (4); Importance Pruning of Algorithm 2 removes the
  *                         incoming connections of neurons whose importance is below a threshold.
  *
@@ -351,6 +353,49 @@ int64_t or_prune_select(int64_t nnz, const float *val, const uint64_t *flat, dou
     remove_smallest(neg_set, n_neg, k_neg, remove);
     free(pos_set); free(neg_set);
     return k_pos + k_neg;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Sparse model averaging, eq. (2): theta_f = (1/K) sum_i theta_i over K replicas whose topologies  */
+/* have diverged; a connection absent from a replica counts as 0.  Input: the T stored entries of   */
+/* all replicas sorted by flat position, entries of equal position in replica order.  Each run of   */
+/* equal positions is added in fp32 in that order and divided by K.  Returns the size of the union. */
+/* The paper then keeps the connections "with bigger magnitude" so that the sparsity level is       */
+/* restored: or_keep_largest marks for removal everything but the n_keep largest (ordering key as   */
+/* in or_prune_select: smaller (|w| bits, flat position) goes first).                               */
+/* ------------------------------------------------------------------------------------------ */
+int64_t or_average_sorted(int64_t T, const uint64_t *flat_sorted, const float *val_sorted, int32_t K,
+                          uint64_t *out_flat, float *out_val)
+{
+    int64_t U = 0;
+    int64_t x = 0;
+    while (x < T) {
+        float s = val_sorted[x];
+        int64_t y = x + 1;
+        while (y < T && flat_sorted[y] == flat_sorted[x]) { s = s + val_sorted[y]; ++y; }
+        out_flat[U] = flat_sorted[x];
+        out_val[U] = s / (float)K;
+        ++U;
+        x = y;
+    }
+    return U;
+}
+
+int64_t or_keep_largest(int64_t n, const float *val, const uint64_t *flat, int64_t n_keep, uint8_t *remove)
+{
+    if (n < 0) return -1;
+    memset(remove, 0, (size_t)n);
+    if (n_keep >= n) return 0;
+    magpos *e = (magpos *)malloc(sizeof(magpos) * (size_t)(n > 0 ? n : 1));
+    if (!e) return -2;
+    for (int64_t p = 0; p < n; ++p) {
+        uint32_t bits;
+        memcpy(&bits, &val[p], 4);
+        e[p].mag = bits & 0x7FFFFFFFu; e[p].pos = flat[p]; e[p].idx = p;
+    }
+    remove_smallest(e, n, n - n_keep, remove);
+    free(e);
+    return n - n_keep;
 }
 
 /* ------------------------------------------------------------------------------------------ */

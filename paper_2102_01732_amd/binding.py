@@ -26,7 +26,7 @@ EXPORTS = [
     "sparse_layer_nnz", "sparse_layer_export_csr", "sparse_layer_import_csr", "sparse_layer_export_grad",
     "sparse_layer_set_lr", "sparse_layer_last_error", "sparse_layer_profile_begin", "sparse_layer_profile_end",
     "sparse_kernel_name", "sparse_layer_link_producer", "sparse_layer_importance", "sparse_layer_importance_prune",
-    "sparse_layer_infer",
+    "sparse_layer_infer", "sparse_layers_average_query", "sparse_layers_average",
 ]
 N_KERNEL_IDS = 7
 
@@ -71,6 +71,8 @@ def lib():
         L.sparse_layer_last_error.argtypes = [vp]
         L.sparse_layer_last_error.restype = C.c_char_p
         L.sparse_layer_link_producer.argtypes = [vp, vp]
+        L.sparse_layers_average_query.argtypes = [i64, C.POINTER(C.c_size_t)]
+        L.sparse_layers_average.argtypes = [vp, C.POINTER(vp), i32, vp, C.c_size_t, vp]
         L.sparse_layer_importance.argtypes = [vp, vp]
         L.sparse_layer_importance_prune.argtypes = [vp, C.c_float, C.POINTER(i64), vp]
         L.sparse_layer_profile_begin.argtypes = [vp]
@@ -223,6 +225,22 @@ class SparseLayer:
             self.close()
         except Exception:
             pass
+
+
+def average_layers(dst: SparseLayer, replicas: Sequence[SparseLayer]):
+    """dst <- sparse average of the replicas (eq. 2), re-pruned by magnitude to dst's number of connections."""
+    total = sum(r.nnz for r in replicas)
+    need = C.c_size_t(0)
+    rc = lib().sparse_layers_average_query(total, C.byref(need))
+    if rc != SL_OK:
+        raise SparseSetError(rc, "sparse_layers_average_query")
+    scratch = torch.empty(need.value + 256, dtype=torch.uint8, device=dst.device)
+    arr = (C.c_void_p * len(replicas))(*[r.handle for r in replicas])
+    dst._check(lib().sparse_layers_average(dst.handle, arr, len(replicas), scratch.data_ptr(), scratch.numel(),
+                                           _stream()), "sparse_layers_average")
+    n = C.c_int64(0)
+    lib().sparse_layer_nnz(dst.handle, C.byref(n))
+    dst.nnz = n.value
 
 
 def softmax_ce(z: torch.Tensor, y: torch.Tensor, B: int, n_classes: int, dz: torch.Tensor,

@@ -380,6 +380,38 @@ int sparse_layer_importance_prune(sl_layer *L, float threshold, int64_t *removed
     return SL_OK;
 }
 
+int sparse_layers_average_query(int64_t total_entries, size_t *scratch_bytes)
+{
+    if (total_entries < 0 || total_entries >= ((int64_t)1 << 32) - 2 || !scratch_bytes) return SL_EINVAL;
+    *scratch_bytes = average_scratch_bytes(total_entries);
+    return SL_OK;
+}
+
+int sparse_layers_average(sl_layer *dst, sl_layer *const *replicas, int32_t K, void *scratch_dev, size_t scratch_bytes,
+                          void *hip_stream)
+{
+    if (!dst || !replicas) return SL_EINVAL;
+    if (K < 1 || K > 16) return set_err(dst, SL_EINVAL, "average: K = %d outside 1..16", K);
+    if (!scratch_dev || ((uintptr_t)scratch_dev & 255)) return set_err(dst, SL_EINVAL, "average: scratch null or not 256-byte aligned");
+    int64_t total = 0;
+    for (int k = 0; k < K; ++k) {
+        const sl_layer *R = replicas[k];
+        if (!R) return set_err(dst, SL_EINVAL, "average: replica %d is null", k);
+        if (R->cfg.n_in != dst->cfg.n_in || R->cfg.n_out != dst->cfg.n_out)
+            return set_err(dst, SL_EINVAL, "average: replica %d has another shape", k);
+        total += R->nnz;
+    }
+    if (total >= ((int64_t)1 << 32) - 2) return set_err(dst, SL_EOVERFLOW, "average: %lld entries in total", (long long)total);
+    hipStream_t s = (hipStream_t)hip_stream;
+    dst->last_stream = s;
+    int rc = topo_average(dst, replicas, K, (char *)scratch_dev, scratch_bytes, s);
+    if (rc) return rc;
+    SL_HIP(dst, hipStreamSynchronize(s));
+    dst->phase = 0;
+    dst->dz_ready = 0;
+    return SL_OK;
+}
+
 static void drop_profile(sl_layer *L)
 {
     for (auto &r : L->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }

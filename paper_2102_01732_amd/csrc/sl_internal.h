@@ -143,6 +143,8 @@ int topo_finalize(sl_layer *L, hipStream_t s);        // vrows + CSC view from t
 int topo_sync_csr_vel(sl_layer *L, hipStream_t s);    // CSC-master layers: velT -> vel (CSR order)
 int topo_sync_csr_grad(sl_layer *L, float *grad_csr_dev, hipStream_t s);
 int topo_check_temp(sl_layer *L, hipStream_t s);      // rocPRIM temporaries fit the reservation
+size_t average_scratch_bytes(int64_t total_entries);
+int topo_average(sl_layer *dst, sl_layer *const *replicas, int K, char *scratch, size_t scratch_bytes, hipStream_t s);
 int topo_importance(sl_layer *L, float *imp_dev, hipStream_t s);
 int topo_importance_prune(sl_layer *L, float threshold, int64_t *removed, hipStream_t s);
 

@@ -511,6 +511,65 @@ __global__ void copy_back_kernel(long n, const int *s_col, const float *s_val, c
 }
 
 // ------------------------------------------------------------------------------------------------
+// Sparse model averaging (eq. 2, last step of Algorithm 1): the stored entries of K replicas are
+// keyed by flat position, sorted stably (equal positions stay in replica order), every run of equal
+// positions is added in fp32 in that order and divided by K (a connection missing from a replica
+// counts as zero), and the union is pruned back by magnitude with the radix select of the evolution.
+// ------------------------------------------------------------------------------------------------
+__global__ void avg_keys_kernel(long n, int n_rows, uint32_t n_in, const int *rowptr, const int *col, const float *val,
+                                long offset, uint64_t *key, uint32_t *pay, float *vals)
+{
+    const long p = (long)blockIdx.x * TB + threadIdx.x;
+    if (p >= n) return;
+    key[offset + p] = (uint64_t)row_of(rowptr, n_rows, (int)p) * n_in + (uint64_t)col[p];
+    pay[offset + p] = (uint32_t)(offset + p);
+    vals[offset + p] = val[p];
+}
+__global__ void avg_head_kernel(long T, const uint64_t *key, uint32_t *head)
+{
+    const long x = (long)blockIdx.x * TB + threadIdx.x;
+    if (x > T) return;
+    head[x] = (x < T && (x == 0 || key[x] != key[x - 1])) ? 1u : 0u;
+}
+__global__ void avg_sum_kernel(long T, const uint64_t *key, const uint32_t *pay, const float *vals, const uint32_t *head,
+                               const uint32_t *uidx, float K, uint64_t *ukey, float *uval)
+{
+    const long x = (long)blockIdx.x * TB + threadIdx.x;
+    if (x >= T || !head[x]) return;
+    const uint64_t k = key[x];
+    float sum = vals[pay[x]];
+    for (long y = x + 1; y < T && key[y] == k; ++y) sum = sum + vals[pay[y]];
+    ukey[uidx[x]] = k;
+    uval[uidx[x]] = sum / K;
+}
+__global__ void avg_compact_kernel(long U, const uint32_t *keep, const uint32_t *kscan, const uint64_t *ukey,
+                                   const float *uval, uint32_t n_in, int *col, float *val, float *vel)
+{
+    const long x = (long)blockIdx.x * TB + threadIdx.x;
+    if (x >= U || !keep[x]) return;
+    const uint32_t d = kscan[x];
+    col[d] = (int)(ukey[x] % n_in);
+    val[d] = uval[x];
+    vel[d] = 0.f;
+}
+__global__ void avg_rowptr_kernel(int n_rows, uint32_t n_in, const uint64_t *ukey, long U, const uint32_t *kscan, int *rowptr)
+{
+    const int r = blockIdx.x * TB + threadIdx.x;
+    if (r > n_rows) return;
+    rowptr[r] = (int)kscan[lower_bound_u64(ukey, U, (uint64_t)r * n_in)];   // kscan[U] = number kept
+}
+struct BiasPtrs { const float *b[16]; };
+__global__ void avg_bias_kernel(int n, BiasPtrs src, int K, float *bias, float *bias_vel)
+{
+    const int j = blockIdx.x * TB + threadIdx.x;
+    if (j >= n) return;
+    float s = src.b[0][j];
+    for (int k = 1; k < K; ++k) s = s + src.b[k][j];
+    bias[j] = s / (float)K;
+    bias_vel[j] = 0.f;
+}
+
+// ------------------------------------------------------------------------------------------------
 // host orchestration
 // ------------------------------------------------------------------------------------------------
 template <typename T>
@@ -722,6 +781,78 @@ int topo_importance_prune(sl_layer *L, float threshold, int64_t *removed, hipStr
     L->nnz = kept;
     if (removed) *removed = n - (long)kept;
     return topo_finalize(L, s);
+}
+
+size_t average_scratch_bytes(int64_t T)
+{
+    const size_t t = (size_t)T + 1;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    // keys A/B, payload A/B, values, head, uidx, ukey, uval, tie, trank, keep, kscan, rocPRIM temporaries
+    return 2 * up(8 * t) + 2 * up(4 * t) + up(4 * t) + 2 * up(4 * t) + up(8 * t) + up(4 * t) + 2 * up(8 * t) + 2 * up(4 * t) +
+           up(((size_t)32 << 20) + 2 * t) + 4096;
+}
+
+int topo_average(sl_layer *D, sl_layer *const *reps, int K, char *scr, size_t scr_bytes, hipStream_t s)
+{
+    const uint32_t n_in = (uint32_t)D->cfg.n_in;
+    const int n_out = (int)D->cfg.n_out;
+    long T = 0;
+    for (int k = 0; k < K; ++k) T += reps[k]->nnz;
+    if (scr_bytes < average_scratch_bytes(T)) return set_err(D, SL_ENOMEM, "average: scratch of %zu bytes needed", average_scratch_bytes(T));
+    const long n_keep = D->nnz;
+    size_t cur = 0;
+    auto take = [&](size_t bytes) { char *p = scr + cur; cur = (cur + bytes + 255) & ~(size_t)255; return p; };
+    const size_t t1 = (size_t)T + 1;
+    uint64_t *kA = (uint64_t *)take(8 * t1), *kB = (uint64_t *)take(8 * t1);
+    uint32_t *vA = (uint32_t *)take(4 * t1), *vB = (uint32_t *)take(4 * t1);
+    float *vals = (float *)take(4 * t1);
+    uint32_t *head = (uint32_t *)take(4 * t1), *uidx = (uint32_t *)take(4 * t1);
+    uint64_t *ukey = (uint64_t *)take(8 * t1);
+    float *uval = (float *)take(4 * t1);
+    uint64_t *tie = (uint64_t *)take(8 * t1), *trank = (uint64_t *)take(8 * t1);
+    uint32_t *keep = (uint32_t *)take(4 * t1), *kscan = (uint32_t *)take(4 * t1);
+    const size_t temp_bytes = ((size_t)32 << 20) + 2 * t1;
+    char *temp = take(temp_bytes);
+    // biases first: they only need the replicas' current values
+    BiasPtrs bp;
+    for (int k = 0; k < K; ++k) bp.b[k] = reps[k]->bias;
+    hipLaunchKernelGGL(avg_bias_kernel, dim3(nblk(n_out)), dim3(TB), 0, s, n_out, bp, K, D->bias, D->bias_vel);
+    if (T == 0) { SL_HIP(D, hipGetLastError()); return SL_OK; }
+    long off = 0;
+    for (int k = 0; k < K; ++k) {
+        const sl_layer *R = reps[k];
+        if (R->nnz > 0)
+            hipLaunchKernelGGL(avg_keys_kernel, dim3(nblk(R->nnz)), dim3(TB), 0, s, (long)R->nnz, n_out, n_in, R->rowptr,
+                               R->colidx, R->val, off, kA, vA, vals);
+        off += R->nnz;
+    }
+    uint64_t *ks; uint32_t *vs;
+    SL_HIP(D, sort_pairs<uint64_t>(temp, temp_bytes, kA, kB, vA, vB, (size_t)T, bit_length((uint64_t)n_in * n_out - 1), &ks, &vs, s));
+    hipLaunchKernelGGL(avg_head_kernel, dim3(nblk(T + 1)), dim3(TB), 0, s, T, ks, head);
+    SL_HIP(D, scan_excl<uint32_t>(temp, temp_bytes, head, uidx, (size_t)T + 1, s));
+    uint32_t U32 = 0;
+    int rc = read_back(D, &U32, uidx + T, sizeof(uint32_t), s);
+    if (rc) return rc;
+    const long U = U32;
+    hipLaunchKernelGGL(avg_sum_kernel, dim3(nblk(T)), dim3(TB), 0, s, T, ks, vs, vals, head, uidx, (float)K, ukey, uval);
+    // prune the union back to n_keep connections: remove the U - n_keep smallest magnitudes
+    const long k_remove = U > n_keep ? U - n_keep : 0;
+    hipLaunchKernelGGL(select_setup_kernel, dim3(2), dim3(256), 0, s, D->sel, (uint32_t)k_remove, 0u);
+    if (k_remove > 0)
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            hipLaunchKernelGGL(select_hist_kernel, dim3(std::min(2048u, nblk(U))), dim3(TB), 0, s, uval, U, 0, shift, D->sel);
+            hipLaunchKernelGGL(select_pick_kernel, dim3(2), dim3(256), 0, s, D->sel, shift == 0 ? 1 : 0);
+        }
+    hipLaunchKernelGGL(tie_flag_kernel, dim3(nblk(U + 1)), dim3(TB), 0, s, uval, U, 0, D->sel, tie);
+    SL_HIP(D, scan_excl<uint64_t>(temp, temp_bytes, tie, trank, (size_t)U + 1, s));
+    hipLaunchKernelGGL(keep_flag_kernel, dim3(nblk(U + 1)), dim3(TB), 0, s, uval, U, 0, D->sel, trank, keep);
+    SL_HIP(D, scan_excl<uint32_t>(temp, temp_bytes, keep, kscan, (size_t)U + 1, s));
+    hipLaunchKernelGGL(avg_compact_kernel, dim3(nblk(U)), dim3(TB), 0, s, U, keep, kscan, ukey, uval, n_in, D->colidx,
+                       D->val, D->vel);
+    hipLaunchKernelGGL(avg_rowptr_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, n_out, n_in, ukey, U, kscan, D->rowptr);
+    SL_HIP(D, hipGetLastError());
+    D->nnz = U - k_remove;
+    return topo_finalize(D, s);
 }
 
 int topo_init(sl_layer *L, hipStream_t s)

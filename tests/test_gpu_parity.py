@@ -597,3 +597,41 @@ def test_weight_decay_term_of_the_update(gpu, oracle):
     # the decay really acts: with zero gradient the weights shrink by lr*lambda*w per step (plus momentum)
     assert lam > 0 and not np.array_equal(val2, val)
     G.close()
+
+
+# ------------------------------------------------------------------------------------------ sparse averaging, eq. (2)
+@pytest.mark.parametrize("n_in,n_out,nnz,K", [(300, 200, 4000, 3), (400, 2, 800, 2), (100000, 70000, 1700000, 4),
+                                               (50, 40, 300, 1)])
+def test_sparse_average_bit_exact(gpu, oracle, n_in, n_out, nnz, K):
+    rng = np.random.default_rng(K + nnz)
+    Gs, Os = [], []
+    for k in range(K):
+        G, O = make_pair(gpu, oracle, n_in, n_out, nnz, seed=500 + k)
+        assert_same_topology(G, O)
+        rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+        val = (rng.standard_normal(nnz) * 0.1).astype(np.float32)
+        if nnz >= 100:
+            val[rng.integers(0, nnz, size=nnz // 20)] = np.float32(0.0625)      # ties across the union
+        bias = rng.standard_normal(n_out).astype(np.float32)
+        vel = rng.standard_normal(nnz).astype(np.float32)
+        G.import_csr(rowptr, colidx, val, vel, bias, bias_vel)
+        O.set_state(rowptr, colidx, val, vel, bias, bias_vel)
+        if k > 0:                                     # let the topologies diverge
+            O.evolve(0.3, k)
+            G.evolve(0.3, k)
+            assert_same_topology(G, O)
+        Gs.append(G)
+        Os.append(O)
+    U = oracle.average_layers(Os[0], Os)
+    gpu.average_layers(Gs[0], Gs)
+    assert Gs[0].nnz == Os[0].nnz == min(nnz, U)
+    assert_same_topology(Gs[0], Os[0])
+    rowptr, colidx, val, vel, bias, bias_vel = Gs[0].export_csr()
+    assert np.array_equal(bias.view(np.uint32), Os[0].bias.view(np.uint32))
+    assert not vel.any() and not bias_vel.any()
+    # the averaged layer is a working layer: it still evolves identically on both sides
+    Os[0].evolve(0.3, 9)
+    Gs[0].evolve(0.3, 9)
+    assert_same_topology(Gs[0], Os[0])
+    for G in Gs:
+        G.close()

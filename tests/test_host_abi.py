@@ -21,7 +21,7 @@ def lib():
 
 def test_exports_match_header(lib):
     header = open(os.path.join(ROOT, "include", "sparse_set.h")).read()
-    declared = set(re.findall(r"\b(sparse_(?:layer|loss|kernel)_\w+)\s*\(", header))
+    declared = set(re.findall(r"\b(sparse_(?:layers?|loss|kernel)_\w+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name

@@ -427,3 +427,39 @@ def test_importance_pruning_removes_exactly_the_weak_neurons(oracle):
     n2 = L2.nnz
     L2.evolve(0.3, 1)
     assert L2.nnz == n2
+
+
+# ---------------------------------------------------------------------------- sparse averaging, eq. (2)
+def test_sparse_average_against_dense_matrices(oracle):
+    n_in, n_out, nnz, K = 30, 20, 150, 3
+    reps = [make_layer(oracle, n_in, n_out, nnz, seed=100 + k) for k in range(K)]
+    rng = np.random.default_rng(12)
+    for r in reps:
+        r.evolve(0.3, 1)                                        # diverged topologies
+        r.bias = rng.standard_normal(n_out).astype(np.float32)
+        r.vel = rng.standard_normal(nnz).astype(np.float32)
+    dense_avg = sum(r.dense() for r in reps) / K               # eq. (2), float64, absent = 0
+    bias_avg = sum(r.bias.astype(np.float64) for r in reps) / K
+    union = int((sum((r.dense() != 0).astype(int) for r in reps) > 0).sum())
+    dst = reps[0]
+    U = oracle.average_layers(dst, reps)
+    assert U == union and union > nnz
+    assert dst.nnz == nnz                                       # sparsity level restored
+    got = dst.dense()
+    kept = got != 0
+    assert np.allclose(got[kept], dense_avg[kept], rtol=1e-6, atol=1e-8)
+    # the kept connections are the nnz largest magnitudes of the average
+    thresh = np.sort(np.abs(dense_avg[dense_avg != 0]))[-nnz]
+    assert np.abs(dense_avg[kept]).min() >= thresh * (1 - 1e-6)
+    assert np.abs(dense_avg[~kept]).max() <= thresh * (1 + 1e-6)
+    assert np.allclose(dst.bias, bias_avg, rtol=1e-6, atol=1e-7)
+    assert not dst.vel.any() and not dst.bias_vel.any()
+    assert np.all(np.diff(dst.flat().astype(np.int64)) > 0)
+    # K = 1 is the identity; identical replicas average to themselves
+    a = make_layer(oracle, n_in, n_out, nnz, seed=7)
+    before = (a.rowptr.copy(), a.colidx.copy(), a.val.copy())
+    assert oracle.average_layers(a, [a]) == nnz
+    assert all(np.array_equal(x, y) for x, y in zip(before, (a.rowptr, a.colidx, a.val)))
+    b, c = make_layer(oracle, n_in, n_out, nnz, seed=7), make_layer(oracle, n_in, n_out, nnz, seed=7)
+    assert oracle.average_layers(b, [b, c]) == nnz
+    assert np.array_equal(b.colidx, before[1]) and np.array_equal(b.val, before[2])
