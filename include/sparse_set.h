@@ -156,6 +156,17 @@ int sparse_layer_destroy(sl_layer *layer);
 int sparse_loss_softmax_ce(const float *z_dev, int64_t ldz, const int32_t *y_dev, int32_t B, int32_t C,
                            float *dz_dev, int64_t lddz, float *loss_sum_dev, void *hip_stream);
 
+/* The same loss written straight into an output layer (identity activation, n_out <= 1024) that has
+ * just run forward with this B: dz and the bias gradient of `layer` are produced here, so its
+ * sparse_layer_backward may be called with grad_a_dev == NULL and needs no separate pass.
+ * z_dev is the a_dev that forward wrote.  Asynchronous. */
+int sparse_loss_softmax_ce_into(sl_layer *layer, const float *z_dev, int64_t ldz, const int32_t *y_dev, int32_t B,
+                                float *loss_sum_dev, void *hip_stream);
+
+/* sparse_layer_update for up to 16 layers in one kernel launch (same arithmetic, same results).
+ * Small networks are bound by the number of dependent launches per step.  Asynchronous. */
+int sparse_layers_update(sl_layer *const *layers, int32_t count, void *hip_stream);
+
 /* Inspection / parity / checkpoint.  Host pointers; each call synchronises the layer's last
  * stream.  Any output pointer may be NULL.  Arrays are in CSR order. */
 int sparse_layer_nnz(const sl_layer *layer, int64_t *nnz);

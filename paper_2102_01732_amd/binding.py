@@ -27,6 +27,7 @@ EXPORTS = [
     "sparse_layer_set_lr", "sparse_layer_last_error", "sparse_layer_profile_begin", "sparse_layer_profile_end",
     "sparse_kernel_name", "sparse_layer_link_producer", "sparse_layer_importance", "sparse_layer_importance_prune",
     "sparse_layer_infer", "sparse_layers_average_query", "sparse_layers_average",
+    "sparse_loss_softmax_ce_into", "sparse_layers_update",
 ]
 N_KERNEL_IDS = 7
 
@@ -73,6 +74,8 @@ def lib():
         L.sparse_layer_link_producer.argtypes = [vp, vp]
         L.sparse_layers_average_query.argtypes = [i64, C.POINTER(C.c_size_t)]
         L.sparse_layers_average.argtypes = [vp, C.POINTER(vp), i32, vp, C.c_size_t, vp]
+        L.sparse_loss_softmax_ce_into.argtypes = [vp, f32p, i64, i32p, i32, f32p, vp]
+        L.sparse_layers_update.argtypes = [C.POINTER(vp), i32, vp]
         L.sparse_layer_importance.argtypes = [vp, vp]
         L.sparse_layer_importance_prune.argtypes = [vp, C.c_float, C.POINTER(i64), vp]
         L.sparse_layer_profile_begin.argtypes = [vp]
@@ -274,6 +277,7 @@ class SparseMLP:
         for li in range(1, len(self.layers)):
             self.layers[li].link_producer(self.layers[li - 1])
         self.grad_out = torch.zeros((layer_specs[-1].n_out, self.ld), dtype=torch.float32, device=self.device)
+        self._handles = (C.c_void_p * len(self.layers))(*[l.handle for l in self.layers])
         self.loss_sum = torch.zeros(1, dtype=torch.float32, device=self.device)
         self.n_classes = layer_specs[-1].n_out
 
@@ -300,12 +304,16 @@ class SparseMLP:
             self.layers[li].backward(xin, self.grad_out if li == last else None, B, None)
 
     def train_step(self, x: torch.Tensor, y: torch.Tensor, B: int):
-        """x [n_in][ld>=B] feature-major, y int32 [B]."""
+        """x [n_in][ld>=B] feature-major, y int32 [B].  Forward, loss written into the output layer,
+        chained backward, one update launch for all layers."""
         zL = self.forward(x, B)
-        softmax_ce(zL, y, B, self.n_classes, self.grad_out, self.loss_sum)
-        self.backward(x, B)
-        for layer in self.layers:
-            layer.update()
+        last = self.layers[-1]
+        last._check(lib().sparse_loss_softmax_ce_into(last.handle, zL.data_ptr(), zL.stride(0), y.data_ptr(), B,
+                                                      self.loss_sum.data_ptr(), _stream()), "sparse_loss_softmax_ce_into")
+        n = len(self.layers)
+        for li in range(n - 1, -1, -1):
+            self.layers[li].backward(x if li == 0 else self.acts[li - 1], None, B, None)
+        last._check(lib().sparse_layers_update(self._handles, n, _stream()), "sparse_layers_update")
 
     def evolve(self, zeta: float, generation: int):
         for layer in self.layers:

@@ -39,13 +39,15 @@ int64_t config_nnz(const sl_config &c)
     return (int64_t)want;
 }
 
-// Rows longer than the returned length are cut into virtual rows.  Wide matrices keep their rows
-// whole unless one is far above the mean; matrices with few rows (narrow output layers) are cut so
-// that about 8192 groups exist.
+// Rows longer than the returned length are cut into virtual rows.  Matrices with at least 64 rows of
+// moderate mean length (every Erdos-Renyi layer) keep their rows whole unless one is far above the
+// mean; matrices with few or very long rows (narrow dense output layers: 2 or 10 rows of up to 10^6
+// entries) are cut so that about 8192 groups exist.
 int choose_seg(int64_t n_rows, int64_t nnz)
 {
+    const int64_t mean = (nnz + n_rows - 1) / (n_rows > 0 ? n_rows : 1);
     int64_t seg;
-    if (n_rows >= 8192) seg = 4 * ((nnz + n_rows - 1) / (n_rows > 0 ? n_rows : 1));
+    if (n_rows >= 64 && mean <= 512) seg = 4 * mean;
     else seg = (nnz + 8191) / 8192;
     if (seg < 64) seg = 64;
     if (seg > (1 << 30)) seg = 1 << 30;
@@ -468,7 +470,38 @@ int sparse_loss_softmax_ce(const float *z_dev, int64_t ldz, const int32_t *y_dev
                            int64_t lddz, float *loss_sum_dev, void *hip_stream)
 {
     if (!z_dev || !y_dev || !dz_dev || B <= 0 || C <= 0 || C > 1024 || ldz < B || lddz < B) return SL_EINVAL;
-    return launch_softmax_ce(z_dev, ldz, y_dev, B, C, dz_dev, lddz, loss_sum_dev, (hipStream_t)hip_stream);
+    return launch_softmax_ce(z_dev, ldz, y_dev, B, C, dz_dev, lddz, loss_sum_dev, nullptr, (hipStream_t)hip_stream);
+}
+
+int sparse_loss_softmax_ce_into(sl_layer *L, const float *z_dev, int64_t ldz, const int32_t *y_dev, int32_t B,
+                                float *loss_sum_dev, void *hip_stream)
+{
+    if (!L) return SL_EINVAL;
+    if (L->cfg.act_kind != 0) return set_err(L, SL_EINVAL, "loss_into: the layer must be an output layer (identity activation)");
+    if (L->phase < 1 || L->last_B != B) return set_err(L, SL_ESTATE, "loss_into: the layer has not run forward with B = %d", B);
+    if (!z_dev || !y_dev || ldz < B || L->cfg.n_out > 1024) return set_err(L, SL_EINVAL, "loss_into: bad argument");
+    L->last_stream = (hipStream_t)hip_stream;
+    int rc = launch_softmax_ce(z_dev, ldz, y_dev, B, (int)L->cfg.n_out, L->dz, L->ldz, loss_sum_dev, L->grad_bias, L->last_stream);
+    if (rc) return set_err(L, rc, "loss_into: launch failed");
+    L->dz_ready = B;
+    return SL_OK;
+}
+
+int sparse_layers_update(sl_layer *const *layers, int32_t count, void *hip_stream)
+{
+    if (!layers || count < 1 || count > SL_MAX_MULTI) return SL_EINVAL;
+    for (int k = 0; k < count; ++k) {
+        if (!layers[k]) return SL_EINVAL;
+        if (layers[k]->phase < 2) return set_err(layers[k], SL_ESTATE, "update called before backward");
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    int rc = launch_update_many(layers, count, s);
+    if (rc) return rc;
+    for (int k = 0; k < count; ++k) {
+        layers[k]->phase = 0;
+        layers[k]->last_stream = s;
+    }
+    return SL_OK;
 }
 
 int sparse_layer_nnz(const sl_layer *L, int64_t *nnz)

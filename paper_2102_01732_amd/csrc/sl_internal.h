@@ -8,6 +8,8 @@
 
 #include "sparse_set.h"
 
+#define SL_MAX_MULTI 16   // layers per multi-layer launch
+
 namespace sl {
 
 // One orientation of the sparse matrix (CSR of Wt for the forward pass, CSC of Wt for the
@@ -134,7 +136,8 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
                     int64_t ldgx, hipStream_t s);
 int launch_update(sl_layer *L, hipStream_t s);
 int launch_softmax_ce(const float *z, int64_t ldz, const int32_t *y, int B, int C, float *dz, int64_t lddz,
-                      float *loss_sum, hipStream_t s);
+                      float *loss_sum, float *gb, hipStream_t s);
+int launch_update_many(sl_layer *const *layers, int count, hipStream_t s);
 
 // topology (sl_topology.hip)
 int topo_init(sl_layer *L, hipStream_t s);

@@ -20,6 +20,7 @@ namespace sl {
 
 static constexpr int BLOCK = 256;
 static constexpr int FIX_BLOCK = 1024;
+static constexpr int MAX_MULTI = SL_MAX_MULTI;
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 __device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
@@ -411,11 +412,55 @@ __global__ __launch_bounds__(BLOCK) void update_kernel(long n, float *w, float *
     }
 }
 
+// The same update for up to MAX_MULTI layers in ONE launch (small networks are bound by the number
+// of dependent launches per step, not by bandwidth).
+struct UpdateOne {
+    long n;          // stored connections
+    long first;      // first global thread index of this layer
+    float *w, *vel;
+    const float *g;
+    const int *scatter_pos;
+    float *w_csr;
+    int nb;
+    float *bias, *bias_vel;
+    const float *gbias;
+    float lr, mu, wd;
+};
+struct UpdateMany {
+    int count;
+    UpdateOne l[MAX_MULTI];
+};
+__global__ __launch_bounds__(BLOCK) void update_many_kernel(UpdateMany a)
+{
+#pragma clang fp contract(off)
+    const long gt = (long)blockIdx.x * BLOCK + threadIdx.x;
+    int k = 0;
+    while (k + 1 < a.count && gt >= a.l[k + 1].first) ++k;
+    const UpdateOne &u = a.l[k];
+    const long t = gt - u.first;
+    if (t < u.n) {
+        const float wt = u.w[t];
+        const float gg = u.g[t] + u.wd * wt;
+        const float vn = u.mu * u.vel[t] - u.lr * gg;
+        const float wn = wt + vn;
+        u.vel[t] = vn;
+        u.w[t] = wn;
+        if (u.scatter_pos) u.w_csr[u.scatter_pos[t]] = wn;
+    } else if (t - u.n < u.nb) {
+        const long j = t - u.n;
+        const float vn = u.mu * u.bias_vel[j] - u.lr * u.gbias[j];
+        u.bias_vel[j] = vn;
+        u.bias[j] = u.bias[j] + vn;
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // Softmax + cross-entropy.  One block; thread t handles samples t, t+blockDim, ...
+// When gb is given (the output layer's bias gradient), the row sums of dz are produced as well, so
+// that the output layer needs no separate activation-derivative pass.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(BLOCK) void softmax_ce_kernel(const float *z, long ldz, const int *y, int B, int C,
-                                                          float *dz, long lddz, float *loss_sum)
+                                                          float *dz, long lddz, float *loss_sum, float *gb)
 {
     __shared__ float red[BLOCK];
     float loss = 0.f;
@@ -440,6 +485,22 @@ __global__ __launch_bounds__(BLOCK) void softmax_ce_kernel(const float *z, long 
         __syncthreads();
     }
     if (threadIdx.x == 0 && loss_sum) *loss_sum += red[0];
+    if (!gb) return;
+    // bias gradient of the output layer: gb[c] = sum_b dz[c][b], one block reduction per class; the
+    // columns B .. roundup4(B)-1 of dz are zeroed for the float4 gathers of the backward kernel
+    for (int c = 0; c < C; ++c) {
+        __syncthreads();
+        float s = 0.f;
+        for (int b = threadIdx.x; b < B; b += BLOCK) s += dz[c * lddz + b];
+        red[threadIdx.x] = s;
+        __syncthreads();
+        for (int m = BLOCK / 2; m >= 1; m >>= 1) {
+            if ((int)threadIdx.x < m) red[threadIdx.x] += red[threadIdx.x + m];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) gb[c] = red[0];
+        if ((int)threadIdx.x < ((B + 3) & ~3) - B) dz[c * lddz + B + threadIdx.x] = 0.f;
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -604,10 +665,32 @@ int launch_update(sl_layer *L, hipStream_t s)
 }
 
 int launch_softmax_ce(const float *z, int64_t ldz, const int32_t *y, int B, int C, float *dz, int64_t lddz,
-                      float *loss_sum, hipStream_t s)
+                      float *loss_sum, float *gb, hipStream_t s)
 {
-    hipLaunchKernelGGL(softmax_ce_kernel, dim3(1), dim3(BLOCK), 0, s, z, (long)ldz, y, B, C, dz, (long)lddz, loss_sum);
+    hipLaunchKernelGGL(softmax_ce_kernel, dim3(1), dim3(BLOCK), 0, s, z, (long)ldz, y, B, C, dz, (long)lddz, loss_sum, gb);
     return hipGetLastError() == hipSuccess ? SL_OK : SL_EHIP;
+}
+
+int launch_update_many(sl_layer *const *layers, int count, hipStream_t s)
+{
+    UpdateMany a;
+    a.count = count;
+    long first = 0;
+    for (int k = 0; k < count; ++k) {
+        sl_layer *L = layers[k];
+        UpdateOne &u = a.l[k];
+        u.n = L->nnz; u.first = first; u.nb = (int)L->cfg.n_out;
+        u.w = L->has_csc ? L->valT : L->val; u.vel = L->has_csc ? L->velT : L->vel; u.g = L->grad;
+        u.scatter_pos = L->has_csc ? L->csr_pos : nullptr; u.w_csr = L->has_csc ? L->val : nullptr;
+        u.bias = L->bias; u.bias_vel = L->bias_vel; u.gbias = L->grad_bias;
+        u.lr = L->cfg.lr; u.mu = L->cfg.momentum; u.wd = L->cfg.weight_decay;
+        // every layer starts on a block boundary so that a block never straddles two layers
+        first += ((u.n + u.nb + BLOCK - 1) / BLOCK) * BLOCK;
+    }
+    ProfScope ps(layers[0], K_UPDATE, s);
+    hipLaunchKernelGGL(update_many_kernel, dim3((unsigned)(first / BLOCK)), dim3(BLOCK), 0, s, a);
+    SL_HIP(layers[0], hipGetLastError());
+    return SL_OK;
 }
 
 }  // namespace sl

@@ -635,3 +635,42 @@ def test_sparse_average_bit_exact(gpu, oracle, n_in, n_out, nnz, K):
     assert_same_topology(Gs[0], Os[0])
     for G in Gs:
         G.close()
+
+
+# ------------------------------------------------------------------------------------------ fewer launches per step
+def test_fused_loss_and_multi_layer_update_match_the_separate_calls(gpu, oracle):
+    import ctypes as C
+    import torch
+    w = wl.WORKLOADS["set_mlp_madelon"]
+    X, y = wl.dataset(w, 100)
+    B = 100                                                  # ragged on purpose
+    x = dev(torch, wl.to_batch_blocks(X, B, ld=128)[0])
+    yd = dev(torch, y)
+    nets = [gpu.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=128)
+            for _ in range(2)]
+    # net 0: separate loss kernel + per-layer updates; net 1: train_step (loss written into the output
+    # layer, one update launch)
+    a = nets[0]
+    zL = a.forward(x, B)
+    gpu.softmax_ce(zL, yd, B, a.n_classes, a.grad_out, a.loss_sum)
+    a.backward(x, B)
+    ga = [L.export_grad() for L in a.layers]
+    for L in a.layers:
+        L.update()
+    b = nets[1]
+    b.train_step(x, yd, B)
+    assert abs(a.loss_sum.item() - b.loss_sum.item()) <= 1e-6 * abs(a.loss_sum.item())
+    for La, Lb, (g, gb) in zip(a.layers, b.layers, ga):
+        ra, rb = La.export_csr(), Lb.export_csr()
+        assert np.array_equal(ra[0], rb[0]) and np.array_equal(ra[1], rb[1])
+        for u, v, what in zip(ra[2:], rb[2:], ("val", "vel", "bias", "bias_vel")):
+            close(v, u, 1e-6, what)
+    # hidden layers see bit-identical dz, so their weights agree bit for bit
+    for La, Lb in zip(a.layers[:-1], b.layers[:-1]):
+        assert np.array_equal(La.export_csr()[2].view(np.uint32), Lb.export_csr()[2].view(np.uint32))
+    # the multi-layer update refuses layers that have no gradient yet
+    h = (C.c_void_p * 1)(a.layers[0].handle)
+    assert gpu.lib().sparse_layers_update(h, 1, None) == gpu.SL_ESTATE
+    assert gpu.lib().sparse_layers_update(h, 0, None) == gpu.SL_EINVAL
+    for n in nets:
+        n.close()
