@@ -104,6 +104,15 @@ int sparse_layer_infer(sl_layer *layer, const float *x_dev, int64_t ldx, int32_t
 int sparse_layer_backward(sl_layer *layer, const float *x_dev, int64_t ldx, const float *grad_a_dev,
                           int64_t ldg, int32_t B, float *grad_x_dev, int64_t ldgx, void *hip_stream);
 
+/* Dropout on the activations of a hidden layer (the paper's experiments use rates 0.3 / 0.4; none of
+ * the benchmark workloads does).  Sets the rate p in [0,1) and the step index that selects the mask
+ * for the NEXT forward/backward pair; call it before every training forward with a new step.  Element
+ * (neuron j, sample b) is kept iff word b&3 of Philox(counter = (j, b>>2, 4, step)) >= floor(p*2^32);
+ * kept activations and their gradients are multiplied by 1/(1-p), dropped ones are zero.  The keep
+ * bits are saved next to the sign bits, so backward needs no regeneration.  sparse_layer_infer never
+ * drops.  p = 0 switches it off. */
+int sparse_layer_set_dropout(sl_layer *layer, float p, uint64_t step);
+
 /* Chaining (optional).  Declares that `layer`'s input x is the activation output of `producer`
  * (same stream, same minibatch).  After that, sparse_layer_backward(layer, ...) may be called with
  * grad_x_dev == NULL: the input gradient is then multiplied by the producer's f' (eq. 3, from its

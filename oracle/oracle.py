@@ -76,6 +76,10 @@ def lib():
         L.or_importance.restype = None
         L.or_importance_f32.argtypes = [c.c_int64, _i32p, _f32p, _f32p]
         L.or_importance_f32.restype = None
+        L.or_dropout_keep.argtypes = [c.c_uint64, c.c_uint32, c.c_uint32, c.c_int64, c.c_int32, c.c_uint32, _u8p]
+        L.or_dropout_keep.restype = None
+        L.or_dropout_apply.argtypes = [_f32p, _u8p, c.c_int64, c.c_float]
+        L.or_dropout_apply.restype = None
         L.or_average_sorted.argtypes = [c.c_int64, _u64p, _f32p, c.c_int32, _u64p, _f32p]
         L.or_average_sorted.restype = c.c_int64
         L.or_keep_largest.argtypes = [c.c_int64, _f32p, _u64p, c.c_int64, _u8p]
@@ -177,6 +181,19 @@ class OracleLayer:
         self.grad_bias = np.zeros(self.n_out, dtype=np.float32)
         self.z: Optional[np.ndarray] = None
         self.dz: Optional[np.ndarray] = None
+        self.drop_p, self.drop_step = np.float32(0.0), 0
+        self.keep: Optional[np.ndarray] = None
+
+    def set_dropout(self, p: float, step: int):
+        """Dropout rate for the next forward/backward pair of this (hidden) layer and the step index
+        that selects the mask."""
+        self.drop_p, self.drop_step = np.float32(p), int(step) & 0xFFFFFFFF
+
+    def dropout_keep(self, B: int) -> np.ndarray:
+        thr = int(np.floor(float(self.drop_p) * 4294967296.0))
+        keep = np.zeros((self.n_out, B), dtype=np.uint8)
+        lib().or_dropout_keep(self.seed, self.layer_id, self.drop_step, self.n_out, B, thr, keep)
+        return keep
 
     @property
     def nnz(self) -> int:
@@ -204,6 +221,11 @@ class OracleLayer:
         lib().or_forward(self.n_out, self.rowptr, self.colidx, self.val, self.bias, x, B, B, self.act_kind,
                          self.act_parity, self.alpha, z, a, B)
         self.z = z
+        self.keep = None
+        if self.drop_p > 0 and self.act_kind != 0:
+            self.keep = self.dropout_keep(B)
+            scale = np.float32(1.0) / (np.float32(1.0) - self.drop_p)
+            lib().or_dropout_apply(a.reshape(-1), self.keep.reshape(-1), a.size, scale)
         return a
 
     def backward(self, x: np.ndarray, grad_a: np.ndarray, need_input_grad: bool = True) -> Optional[np.ndarray]:
@@ -211,6 +233,10 @@ class OracleLayer:
         grad_a = np.ascontiguousarray(grad_a, dtype=np.float32)
         B = x.shape[1]
         assert self.z is not None and self.z.shape == (self.n_out, B) and grad_a.shape == (self.n_out, B)
+        if self.keep is not None:              # the factor of the forward pass multiplies the gradient
+            grad_a = grad_a.copy()
+            scale = np.float32(1.0) / (np.float32(1.0) - self.drop_p)
+            lib().or_dropout_apply(grad_a.reshape(-1), self.keep.reshape(-1), grad_a.size, scale)
         self.dz = np.zeros((self.n_out, B), dtype=np.float32)
         gx = np.zeros((self.n_in, B), dtype=np.float32) if need_input_grad else None
         rc = lib().or_backward(self.n_in, self.n_out, self.rowptr, self.colidx, self.val, x, B, self.z, grad_a,
@@ -333,6 +359,7 @@ class OracleMLP:
         # it to look at pre-activations that sit on the kink of eq. (3), where the branch taken is
         # decided by rounding, and to evaluate the other branch.
         self.after_forward = None
+        self.dropout, self.step_index = 0.0, 0
 
     def forward(self, x: np.ndarray) -> np.ndarray:
         self.acts = [np.ascontiguousarray(x, dtype=np.float32)]
@@ -344,6 +371,10 @@ class OracleMLP:
         return self.acts[-1]
 
     def train_step(self, x: np.ndarray, y: np.ndarray) -> float:
+        if self.dropout > 0.0:
+            for layer in self.layers[:-1]:
+                layer.set_dropout(self.dropout, self.step_index)
+        self.step_index += 1
         zL = self.forward(x)
         loss, grad = softmax_ce(zL, y)
         self.grads = [None] * (len(self.layers) + 1)

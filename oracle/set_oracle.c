@@ -29,6 +29,7 @@
  *                         derivative, weight gradient on existing connections only
  *                         (the worker gradient of Algorithm 1), input gradient.
  *   or_update             momentum SGD, eq. (1), in velocity form.
+ *   or_dropout_keep/apply dropout on hidden activations (experiments' hyper-parameters).
  *   or_prune_select       Algorithm 2's removal step (magnitude based).
  *   or_softmax_ce         softmax + cross-entropy loss and its gradient (loss unnamed in the
  *                         paper; this is the reading used throughout).
@@ -283,6 +284,30 @@ int or_backward(int64_t n_in, int64_t n_out, const int32_t *rowptr, const int32_
         free(acc);
     }
     return 0;
+}
+
+/* Dropout on the activations of a hidden layer (the paper's experiments train with a dropout rate
+ * of 0.3; 0.4 at extreme scale).  Element (neuron j, sample b) is KEPT iff word (b & 3) of the Philox
+ * draw with counter (j, b >> 2, purpose 4, step) is >= thr, thr = floor(p * 2^32); kept activations
+ * are multiplied by scale = 1/(1-p) (inverted dropout), dropped ones are zero.  The same factor
+ * multiplies the gradient that flows back. */
+void or_dropout_keep(uint64_t seed, uint32_t layer_id, uint32_t step, int64_t n_out, int32_t B, uint32_t thr,
+                     uint8_t *keep /* [n_out][B] */)
+{
+    for (int64_t j = 0; j < n_out; ++j)
+        for (int32_t b = 0; b < B; ++b) {
+            uint32_t key[2], ctr[4], w[4];
+            key[0] = (uint32_t)seed ^ (uint32_t)(layer_id * 0x9E3779B9u);
+            key[1] = (uint32_t)(seed >> 32);
+            ctr[0] = (uint32_t)j; ctr[1] = (uint32_t)(b >> 2); ctr[2] = 4u; ctr[3] = step;
+            or_philox4x32_10(ctr, key, w);
+            keep[j * B + b] = w[b & 3] >= thr ? 1 : 0;
+        }
+}
+
+void or_dropout_apply(float *a, const uint8_t *keep, int64_t n, float scale)
+{
+    for (int64_t t = 0; t < n; ++t) a[t] = keep[t] ? a[t] * scale : 0.0f;
 }
 
 /* Momentum SGD, eq. (1): w_{t+1} = w_t + mu (w_t - w_{t-1}) - eta grad.  With vel_t = w_t -

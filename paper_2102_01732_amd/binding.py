@@ -27,7 +27,7 @@ EXPORTS = [
     "sparse_layer_set_lr", "sparse_layer_last_error", "sparse_layer_profile_begin", "sparse_layer_profile_end",
     "sparse_kernel_name", "sparse_layer_link_producer", "sparse_layer_importance", "sparse_layer_importance_prune",
     "sparse_layer_infer", "sparse_layers_average_query", "sparse_layers_average",
-    "sparse_loss_softmax_ce_into", "sparse_layers_update",
+    "sparse_loss_softmax_ce_into", "sparse_layers_update", "sparse_layer_set_dropout",
 ]
 N_KERNEL_IDS = 7
 
@@ -76,6 +76,7 @@ def lib():
         L.sparse_layers_average.argtypes = [vp, C.POINTER(vp), i32, vp, C.c_size_t, vp]
         L.sparse_loss_softmax_ce_into.argtypes = [vp, f32p, i64, i32p, i32, f32p, vp]
         L.sparse_layers_update.argtypes = [C.POINTER(vp), i32, vp]
+        L.sparse_layer_set_dropout.argtypes = [vp, C.c_float, C.c_uint64]
         L.sparse_layer_importance.argtypes = [vp, vp]
         L.sparse_layer_importance_prune.argtypes = [vp, C.c_float, C.POINTER(i64), vp]
         L.sparse_layer_profile_begin.argtypes = [vp]
@@ -146,6 +147,9 @@ class SparseLayer:
     def infer(self, x: torch.Tensor, B: int, a: torch.Tensor):
         self._check(lib().sparse_layer_infer(self.handle, x.data_ptr(), x.stride(0), B, a.data_ptr(), a.stride(0),
                                              _stream()), "sparse_layer_infer")
+
+    def set_dropout(self, p: float, step: int):
+        self._check(lib().sparse_layer_set_dropout(self.handle, float(p), int(step)), "sparse_layer_set_dropout")
 
     def link_producer(self, producer: Optional["SparseLayer"]):
         self._check(lib().sparse_layer_link_producer(self.handle, producer.handle if producer else None),
@@ -280,6 +284,8 @@ class SparseMLP:
         self._handles = (C.c_void_p * len(self.layers))(*[l.handle for l in self.layers])
         self.loss_sum = torch.zeros(1, dtype=torch.float32, device=self.device)
         self.n_classes = layer_specs[-1].n_out
+        self.dropout = 0.0          # rate applied to the hidden layers by train_step (0 = off)
+        self.step_index = 0         # selects the dropout masks; advanced by train_step
 
     def forward(self, x: torch.Tensor, B: int) -> torch.Tensor:
         cur = x
@@ -306,6 +312,10 @@ class SparseMLP:
     def train_step(self, x: torch.Tensor, y: torch.Tensor, B: int):
         """x [n_in][ld>=B] feature-major, y int32 [B].  Forward, loss written into the output layer,
         chained backward, one update launch for all layers."""
+        if self.dropout > 0.0:
+            for layer in self.layers[:-1]:
+                layer.set_dropout(self.dropout, self.step_index)
+        self.step_index += 1
         zL = self.forward(x, B)
         last = self.layers[-1]
         last._check(lib().sparse_loss_softmax_ce_into(last.handle, zL.data_ptr(), zL.stride(0), y.data_ptr(), B,

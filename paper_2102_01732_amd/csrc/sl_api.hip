@@ -285,6 +285,18 @@ int sparse_layer_infer(sl_layer *L, const float *x_dev, int64_t ldx, int32_t B, 
     return launch_forward(L, x_dev, ldx, B, a_dev, lda, false, L->last_stream);
 }
 
+int sparse_layer_set_dropout(sl_layer *L, float p, uint64_t step)
+{
+    if (!L) return SL_EINVAL;
+    if (!(p >= 0.f && p < 1.f)) return set_err(L, SL_EINVAL, "dropout rate %g outside [0,1)", (double)p);
+    if (p > 0.f && L->cfg.act_kind == 0) return set_err(L, SL_EINVAL, "dropout applies to hidden (All-ReLU) layers only");
+    if (L->phase == 1) return set_err(L, SL_ESTATE, "set_dropout between forward and backward");
+    L->drop_thr = (uint32_t)floor((double)p * 4294967296.0);
+    L->drop_scale = 1.0f / (1.0f - p);
+    L->drop_step = (uint32_t)step;
+    return SL_OK;
+}
+
 int sparse_layer_link_producer(sl_layer *L, sl_layer *producer)
 {
     if (!L) return SL_EINVAL;

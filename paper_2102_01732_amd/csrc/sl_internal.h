@@ -92,6 +92,9 @@ struct sl_layer {
     // skips its own activation-derivative pass.
     sl_layer *producer = nullptr;
     int dz_ready = 0;
+    // dropout on this layer's activations for the next forward/backward pair (0 = off)
+    uint32_t drop_thr = 0, drop_step = 0;
+    float drop_scale = 1.f;
     int phase = 0;     // 0 idle, 1 forward done, 2 backward done
     int last_B = 0;
     hipStream_t last_stream = nullptr;
@@ -106,6 +109,27 @@ int set_err(sl_layer *L, int code, const char *fmt, ...);
         hipError_t e__ = (expr);                                                              \
         if (e__ != hipSuccess) return sl::set_err((L), SL_EHIP, "%s: %s", #expr, hipGetErrorString(e__)); \
     } while (0)
+
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies; the key is bumped by
+// two Weyl constants between rounds.
+__host__ __device__ inline void philox(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                       uint32_t out[4])
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t a = (uint64_t)0xD2511F53u * c0;
+        const uint64_t b = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(b >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(a >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)b;
+        c3 = (uint32_t)a;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
 
 // kernel ids reported by the profiling calls
 enum KernelId { K_FWD = 0, K_FWD_FIX, K_ACTGRAD, K_BWD_FUSED, K_SDDMM, K_BWD_FIX, K_UPDATE, K_COUNT };

@@ -24,25 +24,6 @@ struct Rng {
     uint32_t k0, k1, generation;
 };
 
-__host__ __device__ inline void philox(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
-                                       uint32_t out[4])
-{
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const uint64_t a = (uint64_t)0xD2511F53u * c0;
-        const uint64_t b = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(b >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(a >> 32) ^ c3 ^ k1;
-        c1 = (uint32_t)b;
-        c3 = (uint32_t)a;
-        c0 = n0;
-        c2 = n2;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
-}
-
 __device__ inline float fresh_weight(const Rng &r, uint64_t p, float limit)
 {
     uint32_t o[4];

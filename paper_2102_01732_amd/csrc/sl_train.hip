@@ -69,6 +69,10 @@ struct Epi {
     int act_kind;
     float slope;   // -alpha (even layer) or +alpha (odd layer)
     int B;
+    // dropout of the layer that owns the mask: element (row, column b) is kept iff word b&3 of
+    // Philox(row, b>>2, 4, step) >= drop_thr; kept values are multiplied by drop_scale.  0 = off.
+    uint32_t drop_thr, drop_step, k0, k1;
+    float drop_scale;
 };
 
 // Every lane of the group must call this (EPI_DZ reduces across the group).
@@ -81,12 +85,22 @@ __device__ __forceinline__ void finish(const Epi &e, long row, int c, bool activ
         float4 z = make_float4(acc.x + b, acc.y + b, acc.z + b, acc.w + b);
         float4 r = z;
         if (e.act_kind != 0) {
-            const unsigned nib = (z.x > 0.f ? 1u : 0u) | (z.y > 0.f ? 2u : 0u) | (z.z > 0.f ? 4u : 0u) | (z.w > 0.f ? 8u : 0u);
-            if (e.mask_w) e.mask_w[row * e.ldm + (c >> 2)] = (uint8_t)nib;
+            unsigned nib = (z.x > 0.f ? 1u : 0u) | (z.y > 0.f ? 2u : 0u) | (z.z > 0.f ? 4u : 0u) | (z.w > 0.f ? 8u : 0u);
             r.x = z.x > 0.f ? z.x : e.slope * z.x;
             r.y = z.y > 0.f ? z.y : e.slope * z.y;
             r.z = z.z > 0.f ? z.z : e.slope * z.z;
             r.w = z.w > 0.f ? z.w : e.slope * z.w;
+            if (e.drop_thr != 0u && e.mask_w) {   // training forward only; the keep bits go to the high nibble
+                uint32_t o[4];
+                philox((uint32_t)row, (uint32_t)(c >> 2), 4u, e.drop_step, e.k0, e.k1, o);
+                nib |= (o[0] >= e.drop_thr ? 16u : 0u) | (o[1] >= e.drop_thr ? 32u : 0u) |
+                       (o[2] >= e.drop_thr ? 64u : 0u) | (o[3] >= e.drop_thr ? 128u : 0u);
+                r.x = (nib & 16u) ? r.x * e.drop_scale : 0.f;
+                r.y = (nib & 32u) ? r.y * e.drop_scale : 0.f;
+                r.z = (nib & 64u) ? r.z * e.drop_scale : 0.f;
+                r.w = (nib & 128u) ? r.w * e.drop_scale : 0.f;
+            }
+            if (e.mask_w) e.mask_w[row * e.ldm + (c >> 2)] = (uint8_t)nib;
         }
         store_row4(e.out + row * e.ldo, c, e.B, r);
     } else if (e.mode == EPI_PLAIN) {
@@ -97,6 +111,12 @@ __device__ __forceinline__ void finish(const Epi &e, long row, int c, bool activ
             d = acc;
             if (e.act_kind != 0) {
                 const unsigned nib = e.mask_r[row * e.ldm + (c >> 2)];
+                if (e.drop_thr != 0u) {
+                    d.x = (nib & 16u) ? d.x * e.drop_scale : 0.f;
+                    d.y = (nib & 32u) ? d.y * e.drop_scale : 0.f;
+                    d.z = (nib & 64u) ? d.z * e.drop_scale : 0.f;
+                    d.w = (nib & 128u) ? d.w * e.drop_scale : 0.f;
+                }
                 d.x = d.x * ((nib & 1u) ? 1.f : e.slope);
                 d.y = d.y * ((nib & 2u) ? 1.f : e.slope);
                 d.z = d.z * ((nib & 4u) ? 1.f : e.slope);
@@ -543,12 +563,20 @@ static void dispatch_g(int G, F &&f)
 
 static unsigned groups_to_blocks(long n_groups, int G) { return (unsigned)((n_groups + BLOCK / G - 1) / (BLOCK / G)); }
 
+static void set_dropout(Epi &e, const sl_layer *owner)
+{
+    e.drop_thr = owner->drop_thr; e.drop_step = owner->drop_step; e.drop_scale = owner->drop_scale;
+    e.k0 = (uint32_t)owner->cfg.seed ^ (uint32_t)(owner->cfg.layer_id * 0x9E3779B9u);
+    e.k1 = (uint32_t)(owner->cfg.seed >> 32);
+}
+
 static Epi dz_epilogue(sl_layer *owner, int B)
 {
     Epi e;
     e.mode = EPI_DZ; e.out = owner->dz; e.ldo = owner->ldz; e.bias = nullptr; e.mask_w = nullptr;
     e.mask_r = owner->mask; e.ldm = owner->ldm; e.gb = owner->grad_bias; e.act_kind = owner->cfg.act_kind;
     e.slope = owner->cfg.act_parity == 0 ? -owner->cfg.alpha : owner->cfg.alpha; e.B = B;
+    set_dropout(e, owner);
     return e;
 }
 
@@ -576,6 +604,7 @@ int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, in
     Epi &e = f.epi;
     e.mode = EPI_FWD; e.out = a; e.ldo = lda; e.bias = L->bias; e.mask_w = save_sign ? L->mask : nullptr; e.mask_r = nullptr; e.ldm = L->ldm;
     e.gb = nullptr; e.act_kind = L->cfg.act_kind; e.slope = L->cfg.act_parity == 0 ? -L->cfg.alpha : L->cfg.alpha; e.B = B;
+    set_dropout(e, L);
     {
         ProfScope ps(L, K_FWD, s);
         dispatch_gu(G, U, [&](auto g, auto u) {
@@ -618,7 +647,7 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
         } else {
             Epi &e = b.epi;
             e.mode = EPI_PLAIN; e.out = gx; e.ldo = ldgx; e.bias = nullptr; e.mask_w = nullptr; e.mask_r = nullptr;
-            e.ldm = 0; e.gb = nullptr; e.act_kind = 0; e.slope = 0.f; e.B = B;
+            e.ldm = 0; e.gb = nullptr; e.act_kind = 0; e.slope = 0.f; e.B = B; e.drop_thr = 0u;
         }
         {
             ProfScope ps(L, K_BWD_FUSED, s);

@@ -236,10 +236,11 @@ KINK_TAU = 3e-7      # relative to |b| + sum |w||x|: a few fp32 ulps of the term
 MAX_KINKS = 8
 
 
-def oracle_run(oracle, w, blocks, y, n_steps, flips=frozenset()):
+def oracle_run(oracle, w, blocks, y, n_steps, flips=frozenset(), dropout=0.0):
     olayers = [oracle.OracleLayer(s.n_in, s.n_out, s.nnz, s.act_kind, s.act_parity, w.alpha, s.init_limit, w.lr,
                                   w.momentum, 0.0, w.seed, s.layer_id) for s in w.layers]
     onet = oracle.OracleMLP(olayers)
+    onet.dropout = dropout
     seen, state = [], {"step": 0}
 
     def hook(li, layer, a):
@@ -257,6 +258,9 @@ def oracle_run(oracle, w, blocks, y, n_steps, flips=frozenset()):
                 z = layer.z[j, b]
                 layer.z[j, b] = -z if z != 0 else np.float32(1e-30)
                 a[j, b] = oracle.all_relu(layer.z[j:j + 1, b], layer.act_kind, layer.act_parity, layer.alpha)[0]
+                if layer.keep is not None:
+                    scale = np.float32(1.0) / (np.float32(1.0) - layer.drop_p)
+                    a[j, b] = a[j, b] * scale if layer.keep[j, b] else np.float32(0.0)
         return a
 
     onet.after_forward = hook
@@ -288,7 +292,7 @@ def check_network(net, gpu_first, gpu_loss, olayers, losses, first, tol_first, t
         close(bias_vel, O.bias_vel, tol_end, f"bias_vel {li}")
 
 
-def run_network(gpu, oracle, w, n_steps, tol_first=1e-4, tol_end=1e-3):
+def run_network(gpu, oracle, w, n_steps, tol_first=1e-4, tol_end=1e-3, dropout=0.0):
     """Trains n_steps minibatches on both sides from the same initialisation and compares after the
     first step (tol_first) and after the last (tol_end).  Returns the GPU net and the matching oracle."""
     import itertools
@@ -296,6 +300,7 @@ def run_network(gpu, oracle, w, n_steps, tol_first=1e-4, tol_end=1e-3):
     X, y = wl.dataset(w, n_steps * w.batch)
     blocks = wl.to_batch_blocks(X, w.batch)
     net = gpu.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=w.batch)
+    net.dropout = dropout
     xd, yd = dev(torch, blocks), dev(torch, y)
     gpu_first = None
     for k in range(n_steps):
@@ -307,13 +312,13 @@ def run_network(gpu, oracle, w, n_steps, tol_first=1e-4, tol_end=1e-3):
                 _, _, val, vel, bias, _ = G.export_csr()
                 gpu_first.append((net.acts[li].cpu().numpy()[:, :B], val, vel, bias))
     gpu_loss = net.loss_sum.item()
-    onet, olayers, losses, first, seen = oracle_run(oracle, w, blocks, y, n_steps)
+    onet, olayers, losses, first, seen = oracle_run(oracle, w, blocks, y, n_steps, dropout=dropout)
     assert len(seen) <= MAX_KINKS, f"{len(seen)} pre-activations on the kink: pick another seed"
     last_error = None
     for r in range(len(seen) + 1):
         for subset in itertools.combinations(seen, r):
             if r > 0:
-                onet, olayers, losses, first, _ = oracle_run(oracle, w, blocks, y, n_steps, frozenset(subset))
+                onet, olayers, losses, first, _ = oracle_run(oracle, w, blocks, y, n_steps, frozenset(subset), dropout)
             try:
                 check_network(net, gpu_first, gpu_loss, olayers, losses, first, tol_first, tol_end)
                 return net, onet, olayers
@@ -674,3 +679,72 @@ def test_fused_loss_and_multi_layer_update_match_the_separate_calls(gpu, oracle)
     assert gpu.lib().sparse_layers_update(h, 0, None) == gpu.SL_EINVAL
     for n in nets:
         n.close()
+
+
+# ------------------------------------------------------------------------------------------ dropout
+@pytest.mark.parametrize("B,linked", [(128, False), (77, True)])
+def test_dropout_forward_backward(gpu, oracle, B, linked):
+    """Two chained hidden layers with dropout 0.3: identical keep masks (exact zeros in the same
+    places), activations and gradients within 1e-4, with and without handing dz to the producer."""
+    import torch
+    dims, nnz = (300, 500, 400), (4000, 6000)
+    rng = np.random.default_rng(B)
+    Gs, Os = [], []
+    for li in range(2):
+        G, O = make_pair(gpu, oracle, dims[li], dims[li + 1], nnz[li], act_kind=1, parity=li % 2, limit=0.3, seed=21,
+                         layer_id=li, need_input_grad=(li > 0))
+        G.set_dropout(0.3, 11)
+        O.set_dropout(0.3, 11)
+        Gs.append(G)
+        Os.append(O)
+    ld = (B + 3) // 4 * 4
+    x = rng.standard_normal((dims[0], B)).astype(np.float32)
+    ga = rng.standard_normal((dims[2], B)).astype(np.float32)
+    a1 = Os[0].forward(x)
+    a2 = Os[1].forward(a1)
+    g1 = Os[1].backward(a1, ga)
+    Os[0].backward(x, g1, need_input_grad=False)
+    xd, gad = dev(torch, pad_cols(x, ld)), dev(torch, pad_cols(ga, ld))
+    a1d = torch.zeros((dims[1], ld), device="cuda")
+    a2d = torch.zeros((dims[2], ld), device="cuda")
+    Gs[0].forward(xd, B, a1d)
+    Gs[1].forward(a1d, B, a2d)
+    if linked:
+        Gs[1].link_producer(Gs[0])
+        Gs[1].backward(a1d, gad, B, None)
+        Gs[0].backward(xd, None, B, None)
+    else:
+        g1d = torch.zeros((dims[1], ld), device="cuda")
+        Gs[1].backward(a1d, gad, B, g1d)
+        Gs[0].backward(xd, g1d, B, None)
+    for got, ref, O in ((a1d, a1, Os[0]), (a2d, a2, Os[1])):
+        got = got.cpu().numpy()[:, :B]
+        assert np.array_equal(got == 0, ref == 0) and np.array_equal(ref == 0, O.keep == 0)     # same mask
+        assert 0.25 < (ref == 0).mean() < 0.35
+        close(got, ref, 1e-4, "activation with dropout")
+    for G, O in zip(Gs, Os):
+        g, gb = G.export_grad()
+        safe = np.abs(O.z).min(axis=1) > 1e-5
+        assert safe.mean() > 0.9
+        rows = np.repeat(np.arange(O.n_out), np.diff(O.rowptr))
+        if O is Os[0]:      # rows of layer 0 also depend on the kink decisions of layer 1 through g1
+            pass
+        close(g[safe[rows]], O.grad_val[safe[rows]], 2e-4 if O is Os[0] else 1e-4, "grad_val with dropout")
+        close(gb[safe], O.grad_bias[safe], 2e-4 if O is Os[0] else 1e-4, "grad_bias with dropout")
+    # inference never drops; rate 0 switches dropout off again
+    inf = torch.zeros((dims[1], ld), device="cuda")
+    Gs[0].infer(xd, B, inf)
+    Os[0].set_dropout(0.0, 0)
+    close(inf.cpu().numpy()[:, :B], Os[0].forward(x), 1e-4, "inference")
+    with pytest.raises(gpu.SparseSetError):
+        Gs[0].set_dropout(1.0, 0)
+    for G in Gs:
+        G.close()
+
+
+def test_network_training_with_dropout(gpu, oracle):
+    """Eight steps of the Madelon-shaped net with dropout 0.3 on the hidden layers (the paper's recipe)."""
+    w = wl.WORKLOADS["set_mlp_madelon"]
+    net, onet, olayers = run_network(gpu, oracle, w, 8, tol_first=1e-4, tol_end=3e-4, dropout=0.3)
+    assert net.step_index == 8 and onet.step_index == 8
+    net.close()

@@ -463,3 +463,52 @@ def test_sparse_average_against_dense_matrices(oracle):
     b, c = make_layer(oracle, n_in, n_out, nnz, seed=7), make_layer(oracle, n_in, n_out, nnz, seed=7)
     assert oracle.average_layers(b, [b, c]) == nnz
     assert np.array_equal(b.colidx, before[1]) and np.array_equal(b.val, before[2])
+
+
+# ---------------------------------------------------------------------------- dropout on hidden activations
+def test_dropout_mask_statistics_and_gradient(oracle):
+    L = make_layer(oracle, 50, 400, 4000, 1, 0, alpha=0.6, seed=77, limit=0.4)
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((50, 64)).astype(np.float32)
+    a_plain = L.forward(x).copy()
+    p = 0.3
+    L.set_dropout(p, 5)
+    a = L.forward(x)
+    keep = L.keep.astype(bool)
+    assert abs(keep.mean() - (1 - p)) < 4 * np.sqrt(p * (1 - p) / keep.size)       # Bernoulli(1-p)
+    assert abs(keep.mean(axis=0) - (1 - p)).max() < 0.12 and abs(keep.mean(axis=1) - (1 - p)).max() < 0.25
+    scale = np.float32(1) / (np.float32(1) - np.float32(p))
+    assert np.array_equal(a[keep], (a_plain[keep] * scale).astype(np.float32)) and np.all(a[~keep] == 0)
+    # same (seed, layer, step) -> same mask; another step or layer -> another mask
+    assert np.array_equal(L.dropout_keep(64), L.keep)
+    L.set_dropout(p, 6)
+    assert not np.array_equal(L.dropout_keep(64), keep)
+    # inverted dropout keeps the expectation: average over many steps approaches the plain activation
+    acc = np.zeros_like(a_plain, dtype=np.float64)
+    for step in range(300):
+        L.set_dropout(p, 1000 + step)
+        acc += L.forward(x)
+    err = np.abs(acc / 300 - a_plain).mean() / np.abs(a_plain).mean()
+    assert err < 0.06
+    # gradient: with the mask taken as a constant, central differences of sum(c * a_drop) in every weight
+    L.set_dropout(p, 5)
+    c = rng.standard_normal((400, 64)).astype(np.float32)
+    L.forward(x)
+    L.backward(x, c)
+    W, b = L.dense(), L.bias.astype(np.float64)
+    m = L.keep.astype(np.float64) * float(scale)
+
+    def objective(Wd):
+        z = Wd @ x.astype(np.float64) + b[:, None]
+        assert np.abs(z).min() > 1e-7
+        return float((c * m * np.where(z > 0, z, -np.float64(np.float32(0.6)) * z)).sum())
+
+    rows = np.repeat(np.arange(400), np.diff(L.rowptr))
+    for pidx in range(0, L.nnz, 97):
+        W2 = W.copy(); W2[rows[pidx], L.colidx[pidx]] += 1e-4
+        W3 = W.copy(); W3[rows[pidx], L.colidx[pidx]] -= 1e-4
+        fd = (objective(W2) - objective(W3)) / 2e-4
+        assert abs(fd - L.grad_val[pidx]) <= 2e-4 * max(1.0, abs(fd))
+    # p = 0 switches it off
+    L.set_dropout(0.0, 9)
+    assert np.array_equal(L.forward(x), a_plain)
