@@ -403,6 +403,65 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Span kernel for the forward pass of matrices whose rows are very short (mean <= 3 entries: the
+// epsilon = 1 layers).  The backward kernels keep one row per group: their span variants were measured
+// slower (register pressure).  A group owns R = 4 CONSECUTIVE rows and walks their
+// entries as one stream in chunks of 8, so eight row gathers are in flight whatever the individual
+// row lengths are and no gather slot is padding.  Which of the four rows an entry belongs to follows
+// from the five row pointers held in registers; each row's accumulator takes the entry with a weight
+// that is zero for the other rows.  Same arithmetic per row, in the same order, as the row kernels.
+// ------------------------------------------------------------------------------------------------
+static constexpr int SPAN_R = 4;
+static constexpr int SPAN_U = 8;
+
+template <int G>
+__global__ __launch_bounds__(BLOCK) void fwd_span_kernel(FwdArgs a)
+{
+    constexpr int R = SPAN_R, U = SPAN_U;
+    const int lane = threadIdx.x % G;
+    const long r0 = ((long)blockIdx.x * (BLOCK / G) + threadIdx.x / G) * R;
+    const int c = (blockIdx.y * G + lane) * 4;
+    if (r0 >= a.nv || c >= a.epi.B) return;
+    int pp[R + 1];
+#pragma unroll
+    for (int r = 0; r <= R; ++r) pp[r] = a.vptr[min(r0 + r, (long)a.nv)];
+    const float *xb = a.x + c;
+    float4 acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[r] = zero4();
+    const int p1 = pp[R];
+    for (int p = pp[0]; p < p1; p += U) {
+        int cc[U];
+        float ww[U];
+        float4 xv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int q = min(p + u, p1 - 1);
+            cc[u] = a.idx[q];
+            ww[u] = (p + u < p1) ? a.w[q] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) xv[u] = ld4(xb + (long)cc[u] * a.ldx);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int q = p + u;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const bool mine = q >= pp[r] && q < pp[r + 1];   // selected, not multiplied by zero: other rows
+                acc[r].x = mine ? fmaf(ww[u], xv[u].x, acc[r].x) : acc[r].x;   // must not see this entry at all
+                acc[r].y = mine ? fmaf(ww[u], xv[u].y, acc[r].y) : acc[r].y;
+                acc[r].z = mine ? fmaf(ww[u], xv[u].z, acc[r].z) : acc[r].z;
+                acc[r].w = mine ? fmaf(ww[u], xv[u].w, acc[r].w) : acc[r].w;
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+        if (r0 + r < a.nv) finish<G>(a.epi, r0 + r, c, true, acc[r], lane, 0);
+}
+
 // ------------------------------------------------------------------------------------------------
 // Momentum SGD, eq. (1) in velocity form, over the stored connections and the biases.  The
 // products are rounded separately (no fused multiply-add) so that the result is the plain fp32
@@ -527,6 +586,9 @@ __global__ __launch_bounds__(BLOCK) void softmax_ce_kernel(const float *z, long 
 // host launchers
 // ------------------------------------------------------------------------------------------------
 static int group_width(int B) { return B <= 32 ? 8 : B <= 64 ? 16 : B <= 128 ? 32 : 64; }
+// rows so short that four of them are walked as one stream (span kernels)
+static bool use_span(const SegMat &m, long nnz) { return !m.split && m.nv >= 64 && (double)nnz <= 3.0 * (double)m.nv; }
+
 static int chunk_width(const SegMat &m, long nnz)
 {
     const double mean = m.nv > 0 ? (double)nnz / (double)m.nv : 0.0;
@@ -607,11 +669,19 @@ int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, in
     set_dropout(e, L);
     {
         ProfScope ps(L, K_FWD, s);
-        dispatch_gu(G, U, [&](auto g, auto u) {
-            constexpr int GG = decltype(g)::value, UU = decltype(u)::value;
-            dim3 grid(groups_to_blocks(m.nv, GG), (unsigned)tiles);
-            hipLaunchKernelGGL((fwd_kernel<GG, UU>), grid, dim3(BLOCK), 0, s, f);
-        });
+        if (use_span(m, L->nnz)) {
+            dispatch_g(G, [&](auto g) {
+                constexpr int GG = decltype(g)::value;
+                dim3 grid(groups_to_blocks((m.nv + SPAN_R - 1) / SPAN_R, GG), (unsigned)tiles);
+                hipLaunchKernelGGL(fwd_span_kernel<GG>, grid, dim3(BLOCK), 0, s, f);
+            });
+        } else {
+            dispatch_gu(G, U, [&](auto g, auto u) {
+                constexpr int GG = decltype(g)::value, UU = decltype(u)::value;
+                dim3 grid(groups_to_blocks(m.nv, GG), (unsigned)tiles);
+                hipLaunchKernelGGL((fwd_kernel<GG, UU>), grid, dim3(BLOCK), 0, s, f);
+            });
+        }
     }
     if (m.split) launch_fix(L, m, e, G, K_FWD_FIX, s);
     SL_HIP(L, hipGetLastError());

@@ -96,7 +96,10 @@ def test_init_topology_bit_exact(gpu, oracle, n_in, n_out, nnz):
     (3000, 10, 30000, 80, 128, 0, 0, True),       # dense output layer, rows of 3000
     (6, 2000, 12000, 128, 128, 1, 0, True),       # long columns: the CSC side is split
     (3000, 5000, 37, 128, 128, 1, 0, True),       # mostly empty rows and columns
-    (2000, 3000, 90000, 128, 128, 1, 0, True)])
+    (2000, 3000, 90000, 128, 128, 1, 0, True),
+    (2000, 3001, 6000, 128, 128, 1, 0, True),     # rows of about two entries: span kernels, ragged last span
+    (2000, 3001, 6000, 30, 32, 1, 1, False),      # span SDDMM, G = 8, ragged batch
+    (1500, 2500, 5000, 300, 512, 1, 0, True)])    # span kernels with two batch tiles
 def test_forward_backward_update_one_layer(gpu, oracle, n_in, n_out, nnz, B, max_batch, act_kind, parity, need_gx):
     import torch
     G, O = make_pair(gpu, oracle, n_in, n_out, nnz, act_kind=act_kind, parity=parity, max_batch=max_batch,
