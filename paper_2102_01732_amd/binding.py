@@ -329,6 +329,30 @@ class SparseMLP:
         for layer in self.layers:
             layer.evolve(zeta, generation)
 
+    def fit(self, blocks: torch.Tensor, labels: torch.Tensor, sizes: Sequence[int], epochs: int, zeta: float, *,
+            importance_every: int = 0, importance_start: int = 0, importance_quantile: float = 0.0,
+            first_generation: int = 1):
+        """The training loop of Algorithm 2 over library calls: per epoch, every minibatch block is
+        trained on; then (optionally, every `importance_every` epochs from epoch `importance_start`
+        on) Importance Pruning removes the incoming connections of the hidden neurons whose
+        importance lies below the `importance_quantile` quantile of their layer; then every layer goes
+        through the prune / regrow cycle.  blocks [n_blocks][n_in][ld], labels int32 [n_blocks][ld>=B],
+        sizes[k] = number of samples in block k.  Returns the mean loss of every epoch."""
+        history = []
+        for e in range(epochs):
+            self.loss_sum.zero_()
+            for k in range(blocks.shape[0]):
+                self.train_step(blocks[k], labels[k], sizes[k])
+            history.append(self.loss_sum.item() / float(sum(sizes)))
+            if importance_every > 0 and e >= importance_start and (e - importance_start) % importance_every == 0:
+                for layer in self.layers[:-1]:
+                    imp = layer.importance()
+                    alive = imp[imp > 0]
+                    if alive.size:
+                        layer.importance_prune(float(np.quantile(alive.astype(np.float64), importance_quantile)))
+            self.evolve(zeta, first_generation + e)
+        return history
+
     def close(self):
         for layer in self.layers:
             layer.close()

@@ -751,3 +751,44 @@ def test_network_training_with_dropout(gpu, oracle):
     net, onet, olayers = run_network(gpu, oracle, w, 8, tol_first=1e-4, tol_end=3e-4, dropout=0.3)
     assert net.step_index == 8 and onet.step_index == 8
     net.close()
+
+
+# ------------------------------------------------------------------------------------------ end to end
+def test_training_learns_and_is_reproducible(gpu):
+    """Eight epochs of Algorithm 2 (train, Importance Pruning from epoch 5, prune/regrow) on the
+    Madelon-shaped workload: the loss falls, accuracy on the training data beats chance clearly, nnz
+    only changes through Importance Pruning, and a second run gives the same bits.  The epochs of
+    this workload are only 32 steps long, so a small evolution fraction is used (with zeta = 0.3 and
+    so few steps between rewirings the loss does not settle)."""
+    import torch
+    w = wl.WORKLOADS["set_mlp_madelon"]
+    X, y = wl.dataset(w)
+    B = w.batch
+    blocks = dev(torch, wl.to_batch_blocks(X, B))
+    labels = dev(torch, y.reshape(-1, B))
+    sizes = [B] * blocks.shape[0]
+
+    def run():
+        net = gpu.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=B)
+        hist = net.fit(blocks, labels, sizes, 8, 0.02, importance_every=1, importance_start=5, importance_quantile=0.02)
+        outs = [torch.zeros_like(a) for a in net.acts]
+        correct = 0
+        for k in range(blocks.shape[0]):
+            z = net.infer(blocks[k], B, outs)
+            correct += int((z[:, :B].argmax(dim=0).to(torch.int32) == labels[k]).sum().item())
+        state = [L.export_csr() for L in net.layers]
+        nnz = [L.nnz for L in net.layers]
+        net.close()
+        return hist, correct / float(B * blocks.shape[0]), state, nnz
+
+    hist, acc, state, nnz = run()
+    assert all(np.isfinite(hist)) and hist[-1] < 0.8 * hist[0], hist
+    assert acc > 0.6, acc
+    assert nnz[-1] == w.layers[-1].nnz                               # the output layer is never importance-pruned
+    assert all(n <= s.nnz for n, s in zip(nnz, w.layers)) and sum(nnz) < sum(s.nnz for s in w.layers)
+    hist2, acc2, state2, nnz2 = run()
+    assert hist2 == hist and acc2 == acc and nnz2 == nnz
+    for a, b in zip(state, state2):
+        for u, v in zip(a, b):
+            assert np.array_equal(u.view(np.uint32) if u.dtype == np.float32 else u,
+                                  v.view(np.uint32) if v.dtype == np.float32 else v)
