@@ -158,6 +158,19 @@ int sparse_layers_average(sl_layer *dst, sl_layer *const *replicas, int32_t K, v
 
 int sparse_layer_destroy(sl_layer *layer);
 
+/* RetainValidUpdates of Algorithm 1 (asynchronous training on a parameter server): a gradient that
+ * was computed on an older topology of this layer is restricted to the connections that still
+ * exist; connections created since get a zero gradient.  The old pattern is CSR (old_rowptr_dev
+ * int32[n_out+1], old_colidx_dev int32[old_nnz], columns ascending within a row) with
+ * old_grad_dev float[old_nnz] in the same order and old_grad_bias_dev float[n_out]; all device
+ * pointers, borrowed for the call's kernels only.  The result becomes the layer's pending gradient,
+ * exactly as if sparse_layer_backward had produced it: sparse_layer_update applies it and
+ * sparse_layer_export_grad reads it.  Row bounds outside [0, old_nnz] are clamped, never followed.
+ * SL_ESTATE between forward and backward.  Asynchronous. */
+int sparse_layer_retain_valid_updates(sl_layer *layer, const int32_t *old_rowptr_dev, const int32_t *old_colidx_dev,
+                                      const float *old_grad_dev, int64_t old_nnz, const float *old_grad_bias_dev,
+                                      void *hip_stream);
+
 /* Softmax + cross-entropy over C output neurons (the loss is unnamed in the paper).
  * z_dev [C][ldz], y_dev int32[B] (device) -> dz_dev [C][lddz] = (softmax(z) - onehot(y)) / B and
  * *loss_sum_dev += sum_b -log softmax(z)[y_b] (device float; the caller zeroes and averages it;

@@ -348,6 +348,23 @@ def average_layers(dst: OracleLayer, replicas: Sequence[OracleLayer]) -> int:
     return int(U)
 
 
+def retain_valid_updates(layer: OracleLayer, old_rowptr: np.ndarray, old_colidx: np.ndarray, old_grad: np.ndarray,
+                         old_grad_bias: np.ndarray):
+    """RetainValidUpdates of Algorithm 1: a gradient that a worker computed on an older topology is
+    restricted to the connections that still exist; connections created since then get a zero
+    gradient.  The result becomes the layer's pending gradient (layer.update() applies it)."""
+    old_flat = flat_from_csr(np.asarray(old_rowptr, np.int32), np.asarray(old_colidx, np.int32), layer.n_in)
+    new_flat = layer.flat()
+    g = np.zeros(layer.nnz, dtype=np.float32)
+    if old_flat.size and new_flat.size:
+        pos = np.searchsorted(old_flat, new_flat)
+        pos_c = np.minimum(pos, old_flat.size - 1)
+        hit = old_flat[pos_c] == new_flat
+        g[hit] = np.asarray(old_grad, np.float32)[pos_c[hit]]
+    layer.grad_val = g
+    layer.grad_bias = np.asarray(old_grad_bias, np.float32).copy()
+
+
 # ----------------------------------------------------------------------------------------------
 # a sparse MLP = chain of layers + softmax cross-entropy
 # ----------------------------------------------------------------------------------------------

@@ -28,6 +28,7 @@ EXPORTS = [
     "sparse_kernel_name", "sparse_layer_link_producer", "sparse_layer_importance", "sparse_layer_importance_prune",
     "sparse_layer_infer", "sparse_layers_average_query", "sparse_layers_average",
     "sparse_loss_softmax_ce_into", "sparse_layers_update", "sparse_layer_set_dropout",
+    "sparse_layer_retain_valid_updates",
 ]
 N_KERNEL_IDS = 7
 
@@ -78,6 +79,7 @@ def lib():
         L.sparse_layers_update.argtypes = [C.POINTER(vp), i32, vp]
         L.sparse_layer_set_dropout.argtypes = [vp, C.c_float, C.c_uint64]
         L.sparse_layer_importance.argtypes = [vp, vp]
+        L.sparse_layer_retain_valid_updates.argtypes = [vp, i32p, i32p, f32p, i64, f32p, vp]
         L.sparse_layer_importance_prune.argtypes = [vp, C.c_float, C.POINTER(i64), vp]
         L.sparse_layer_profile_begin.argtypes = [vp]
         L.sparse_layer_profile_end.argtypes = [vp, vp, vp, i32]
@@ -168,6 +170,18 @@ class SparseLayer:
     def evolve(self, zeta: float, generation: int):
         self._check(lib().sparse_layer_evolve(self.handle, float(zeta), int(generation), _stream()),
                     "sparse_layer_evolve")
+
+    def retain_valid_updates(self, old_rowptr: torch.Tensor, old_colidx: torch.Tensor, old_grad: torch.Tensor,
+                             old_grad_bias: torch.Tensor):
+        """Device tensors: int32 CSR pattern of an older topology, its gradient in that order, the bias gradient."""
+        assert old_rowptr.dtype == torch.int32 and old_colidx.dtype == torch.int32 and old_rowptr.numel() == self.n_out + 1
+        assert old_grad.dtype == torch.float32 and old_grad.numel() == old_colidx.numel()
+        assert old_grad_bias.dtype == torch.float32 and old_grad_bias.numel() == self.n_out
+        assert all(t.is_cuda and t.is_contiguous() for t in (old_rowptr, old_colidx, old_grad, old_grad_bias))
+        self._check(lib().sparse_layer_retain_valid_updates(self.handle, old_rowptr.data_ptr(), old_colidx.data_ptr(),
+                                                            old_grad.data_ptr(), old_colidx.numel(),
+                                                            old_grad_bias.data_ptr(), _stream()),
+                    "sparse_layer_retain_valid_updates")
 
     def importance(self) -> np.ndarray:
         out = np.zeros(self.n_out, np.float32)

@@ -370,6 +370,25 @@ int sparse_layer_evolve(sl_layer *L, double zeta, uint64_t generation, void *hip
     return SL_OK;
 }
 
+int sparse_layer_retain_valid_updates(sl_layer *L, const int32_t *old_rowptr_dev, const int32_t *old_colidx_dev,
+                                      const float *old_grad_dev, int64_t old_nnz, const float *old_grad_bias_dev,
+                                      void *hip_stream)
+{
+    if (!L) return SL_EINVAL;
+    if (!old_rowptr_dev || !old_grad_bias_dev) return set_err(L, SL_EINVAL, "retain_valid_updates: null rowptr or bias gradient");
+    if (old_nnz < 0 || old_nnz > INT32_MAX) return set_err(L, SL_EINVAL, "retain_valid_updates: old_nnz = %lld", (long long)old_nnz);
+    if (old_nnz > 0 && (!old_colidx_dev || !old_grad_dev)) return set_err(L, SL_EINVAL, "retain_valid_updates: null colidx or gradient");
+    if (L->phase == 1) return set_err(L, SL_ESTATE, "retain_valid_updates between forward and backward");
+    L->last_stream = (hipStream_t)hip_stream;
+    int rc = topo_retain_valid(L, old_rowptr_dev, old_colidx_dev, old_grad_dev, old_nnz, L->last_stream);
+    if (rc) return rc;
+    SL_HIP(L, hipMemcpyAsync(L->grad_bias, old_grad_bias_dev, sizeof(float) * (size_t)L->cfg.n_out, hipMemcpyDeviceToDevice,
+                             L->last_stream));
+    L->phase = 2;
+    L->dz_ready = 0;
+    return SL_OK;
+}
+
 int sparse_layer_importance(sl_layer *L, float *importance_host)
 {
     if (!L || !importance_host) return SL_EINVAL;

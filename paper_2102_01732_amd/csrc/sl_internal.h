@@ -172,6 +172,8 @@ int topo_sync_csr_grad(sl_layer *L, float *grad_csr_dev, hipStream_t s);
 int topo_check_temp(sl_layer *L, hipStream_t s);      // rocPRIM temporaries fit the reservation
 size_t average_scratch_bytes(int64_t total_entries);
 int topo_average(sl_layer *dst, sl_layer *const *replicas, int K, char *scratch, size_t scratch_bytes, hipStream_t s);
+int topo_retain_valid(sl_layer *L, const int *old_rowptr, const int *old_col, const float *old_grad, int64_t old_nnz,
+                      hipStream_t s);
 int topo_importance(sl_layer *L, float *imp_dev, hipStream_t s);
 int topo_importance_prune(sl_layer *L, float threshold, int64_t *removed, hipStream_t s);
 

@@ -724,6 +724,35 @@ static int rebuild(sl_layer *L, long ns, long k, uint32_t generation, hipStream_
     return topo_finalize(L, s);
 }
 
+// RetainValidUpdates (Algorithm 1): the gradient of master entry t is the old gradient of the same
+// (row, column) if the old pattern has it, else zero.  Row bounds read from the caller's rowptr are
+// clamped to [0, old_nnz], so a malformed old pattern cannot send the search out of bounds.
+__global__ void retain_valid_kernel(long n, int n_rows, const int *rowptr, const int *colidx, const int *rowidx,
+                                    const int *csr_pos, const int *old_rowptr, const int *old_col, const float *old_grad,
+                                    int old_nnz, float *grad)
+{
+    const long t = blockIdx.x * (long)TB + threadIdx.x;
+    if (t >= n) return;
+    const int p = csr_pos ? csr_pos[t] : (int)t;
+    const int j = rowidx ? rowidx[t] : row_of(rowptr, n_rows, p);
+    const int i = colidx[p];
+    const int lo = min(max(old_rowptr[j], 0), old_nnz);
+    const int hi = min(max(old_rowptr[j + 1], lo), old_nnz);
+    const int q = lower_bound_i32(old_col, lo, hi, i);
+    grad[t] = (q < hi && old_col[q] == i) ? old_grad[q] : 0.f;
+}
+
+int topo_retain_valid(sl_layer *L, const int *old_rowptr, const int *old_col, const float *old_grad, int64_t old_nnz,
+                      hipStream_t s)
+{
+    if (L->nnz == 0) return SL_OK;
+    hipLaunchKernelGGL(retain_valid_kernel, dim3(nblk(L->nnz)), dim3(TB), 0, s, (long)L->nnz, (int)L->cfg.n_out, L->rowptr,
+                       L->colidx, L->has_csc ? L->rowidx : nullptr, L->has_csc ? L->csr_pos : nullptr, old_rowptr, old_col,
+                       old_grad, (int)old_nnz, L->grad);
+    SL_HIP(L, hipGetLastError());
+    return SL_OK;
+}
+
 int topo_importance(sl_layer *L, float *imp_dev, hipStream_t s)
 {
     hipLaunchKernelGGL(importance_kernel, dim3(nblk(L->cfg.n_out)), dim3(TB), 0, s, (int)L->cfg.n_out, L->rowptr, L->val,

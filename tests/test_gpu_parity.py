@@ -456,6 +456,47 @@ def test_importance_pruning_bit_exact(gpu, oracle, n_in, n_out, nnz, need_gx):
     G.close()
 
 
+# ------------------------------------------------------------------ RetainValidUpdates (Algorithm 1)
+@pytest.mark.parametrize("n_in,n_out,nnz,need_gx", [(500, 400, 9000, True), (500, 400, 9000, False),
+                                                     (64, 3, 100, True), (100000, 70000, 1700000, True)])
+def test_retain_valid_updates_bit_exact(gpu, oracle, n_in, n_out, nnz, need_gx):
+    import torch
+    G, O = make_pair(gpu, oracle, n_in, n_out, nnz, need_input_grad=need_gx, seed=43)
+    rng = np.random.default_rng(nnz + 5)
+    old_rowptr, old_colidx = O.rowptr.copy(), O.colidx.copy()
+    old_grad = rng.standard_normal(nnz).astype(np.float32)
+    old_gb = rng.standard_normal(n_out).astype(np.float32)
+    for gen in (1, 2):                                      # the topology moves on twice
+        O.evolve(0.3, gen)
+        G.evolve(0.3, gen)
+    assert_same_topology(G, O)
+    oracle.retain_valid_updates(O, old_rowptr, old_colidx, old_grad, old_gb)
+    G.retain_valid_updates(dev(torch, old_rowptr), dev(torch, old_colidx), dev(torch, old_grad), dev(torch, old_gb))
+    g, gb = G.export_grad()
+    assert np.array_equal(g.view(np.uint32), O.grad_val.view(np.uint32))
+    assert np.array_equal(gb.view(np.uint32), O.grad_bias.view(np.uint32))
+    assert 0 < (g == 0).sum() < nnz
+    O.update()
+    G.update()
+    assert_same_topology(G, O)
+    # an empty old pattern retains nothing; a pattern identical to the current one retains everything
+    zero_ptr = np.zeros(n_out + 1, np.int32)
+    G.retain_valid_updates(dev(torch, zero_ptr), torch.zeros(0, dtype=torch.int32, device="cuda"),
+                           torch.zeros(0, device="cuda"), dev(torch, old_gb))
+    g, _ = G.export_grad()
+    assert not g.any()
+    G.update()
+    O.grad_val = np.zeros(O.nnz, np.float32)
+    O.grad_bias = old_gb.copy()
+    O.update()
+    assert_same_topology(G, O)
+    same = rng.standard_normal(O.nnz).astype(np.float32)
+    G.retain_valid_updates(dev(torch, O.rowptr), dev(torch, O.colidx), dev(torch, same), dev(torch, old_gb))
+    g, _ = G.export_grad()
+    assert np.array_equal(g, same)
+    G.close()
+
+
 def gpu_bias_act(bias, O, B):
     z = np.repeat(np.asarray(bias, np.float32)[:, None], B, axis=1)
     return np.where(z > 0, z, (-O.alpha if O.act_parity == 0 else O.alpha) * z).astype(np.float32)

@@ -512,3 +512,26 @@ def test_dropout_mask_statistics_and_gradient(oracle):
     # p = 0 switches it off
     L.set_dropout(0.0, 9)
     assert np.array_equal(L.forward(x), a_plain)
+
+
+# ---------------------------------------------------------------------------- RetainValidUpdates, Algorithm 1
+def test_retain_valid_updates_against_dense_masking(oracle):
+    L = make_layer(oracle, 40, 30, 400, seed=61)
+    rng = np.random.default_rng(8)
+    old_rowptr, old_colidx = L.rowptr.copy(), L.colidx.copy()
+    old_grad = rng.standard_normal(400).astype(np.float32)
+    old_gb = rng.standard_normal(30).astype(np.float32)
+    dense_old = np.zeros((30, 40))
+    dense_old[np.repeat(np.arange(30), np.diff(old_rowptr)), old_colidx] = old_grad
+    L.evolve(0.3, 1)                                        # the topology moved on since the gradient was computed
+    oracle.retain_valid_updates(L, old_rowptr, old_colidx, old_grad, old_gb)
+    rows = np.repeat(np.arange(30), np.diff(L.rowptr))
+    assert np.array_equal(L.grad_val, dense_old[rows, L.colidx].astype(np.float32))    # absent in the old pattern -> 0
+    old_set = set(zip(np.repeat(np.arange(30), np.diff(old_rowptr)).tolist(), old_colidx.tolist()))
+    fresh = sum((j, i) not in old_set for j, i in zip(rows.tolist(), L.colidx.tolist()))
+    assert (L.grad_val == 0).sum() == fresh and 60 <= fresh <= 120     # 120 regrown, a few onto positions the old pattern had
+    assert np.array_equal(L.grad_bias, old_gb)
+    w_before = L.val.copy()
+    L.update()
+    changed = L.val != w_before
+    assert np.array_equal(changed, L.grad_val != 0)         # brand-new connections are left alone (zero velocity)
