@@ -559,6 +559,9 @@ def test_argument_and_call_order_errors(gpu):
     assert code(lambda: L.backward(x, a, 32, None)) == gpu.SL_EINVAL        # grad_x missing, no producer linked
     assert code(lambda: L.backward(x, None, 32, gx)) == gpu.SL_EINVAL       # grad_a missing, nothing handed over
     assert code(L.export_grad) == gpu.SL_ESTATE
+    rp = torch.zeros(49, dtype=torch.int32, device="cuda")
+    none_i, none_f, gb0 = torch.zeros(0, dtype=torch.int32, device="cuda"), torch.zeros(0, device="cuda"), torch.zeros(48, device="cuda")
+    assert code(lambda: L.retain_valid_updates(rp, none_i, none_f, gb0)) == gpu.SL_ESTATE   # between forward and backward
     L.backward(x, a, 32, gx)
     L.export_grad()
     L.update()
@@ -569,6 +572,14 @@ def test_argument_and_call_order_errors(gpu):
     bad[0] = 64
     assert code(lambda: L.import_csr(rowptr, bad, val)) == gpu.SL_EINVAL
     assert code(lambda: L.import_csr(rowptr[::-1].copy(), colidx, val)) == gpu.SL_EINVAL
+    # an old pattern whose row bounds are nonsense is clamped, never followed: every gradient comes out zero or in range
+    wild = torch.full((49,), 2**31 - 1, dtype=torch.int32, device="cuda")
+    wild[::2] = -5
+    oc = torch.arange(7, dtype=torch.int32, device="cuda")
+    L.retain_valid_updates(wild, oc, torch.ones(7, device="cuda"), gb0)
+    g, _ = L.export_grad()
+    assert set(np.unique(g)) <= {0.0, 1.0}
+    L.update()
     other = gpu.SparseLayer(gpu.make_config(10, 64, nnz=50, init_limit=0.1, max_batch=16, need_input_grad=False))
     assert code(lambda: L.link_producer(other)) == gpu.SL_EINVAL            # producer's max_batch too small
     assert "max_batch" in gpu.lib().sparse_layer_last_error(L.handle).decode()
