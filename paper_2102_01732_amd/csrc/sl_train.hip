@@ -315,6 +315,7 @@ struct BwdArgs {
     long ldp;
     int B;
     int ragged;      // B % 4 != 0
+    int tile0, tile1; // bwd_pair_kernel: the batch tiles this launch covers
     Epi epi;         // SPMM, not split: what to do with the finished grad_x row
 };
 
@@ -398,6 +399,99 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
                 if (active) st4(a.part + v * a.ldp + c, acc);
             } else {
                 finish<G>(a.epi, row, c, active, acc, lane, tile);
+            }
+        }
+    }
+}
+
+
+
+// The same walk for batches above 256 columns: a group of 64 lanes carries T = 2 batch tiles (of 256
+// columns) at once and covers the tiles [tile0, tile1) of its launch.  A lane holds two float4 per gathered
+// row, the two tiles' products are added before the cross-lane reduction, and the per-entry gradient is
+// written once per pair of tiles instead of once per tile.  (Kept apart from bwd_kernel: folding the two
+// into one template cost the single-tile instances twelve registers and one wave of occupancy.)
+template <int U, bool SPMM>
+__global__ __launch_bounds__(BLOCK) void bwd_pair_kernel(BwdArgs a)
+{
+    constexpr int G = 64, T = 2;
+    const int lane = threadIdx.x % G;
+    const long v = (long)blockIdx.x * (BLOCK / G) + threadIdx.x / G;
+    if (v >= a.nv) return;   // whole groups leave together
+    const int p0 = a.vptr[v], p1 = a.vptr[v + 1];
+    const long row = a.v2row ? a.v2row[v] : v;
+    for (int tile = a.tile0; tile < a.tile1; tile += T) {
+        int c[T];
+        bool active[T];
+        float4 h[T], acc[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            c[t] = ((tile + t) * G + lane) * 4;
+            active[t] = c[t] < a.B;
+            h[t] = zero4();
+            if (active[t]) {
+                h[t] = ld4(a.held + row * a.ldh + c[t]);
+                if (a.ragged) h[t] = clip4(h[t], c[t], a.B);
+            }
+            acc[t] = zero4();
+        }
+        for (int p = p0; p < p1; p += U) {
+            int cc[U];
+            float ww[U];
+            float4 xv[U][T];
+            float s[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int q = min(p + u, p1 - 1);
+                cc[u] = a.idx[q];
+                if (SPMM) ww[u] = (p + u < p1) ? a.w[q] : 0.f;
+            }
+            // later batch tiles add to what the earlier ones stored; fetch it with the indices, not after
+            // the reduction, so that its latency hides behind the row gathers
+            const bool writer = lane < U && p + lane < p1;
+            float g_prev = 0.f;
+            if (tile > 0 && writer) g_prev = a.g[p + lane];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    xv[u][t] = zero4();
+                    if (active[t]) {
+                        xv[u][t] = ld4(a.gath + (long)cc[u] * a.ldga + c[t]);
+                        if (a.ragged) xv[u][t] = clip4(xv[u][t], c[t], a.B);
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float d = 0.f;
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    const float4 x4 = xv[u][t];
+                    if (SPMM) {
+                        acc[t].x = fmaf(ww[u], x4.x, acc[t].x);
+                        acc[t].y = fmaf(ww[u], x4.y, acc[t].y);
+                        acc[t].z = fmaf(ww[u], x4.z, acc[t].z);
+                        acc[t].w = fmaf(ww[u], x4.w, acc[t].w);
+                    }
+                    const float dt = fmaf(h[t].x, x4.x, fmaf(h[t].y, x4.y, fmaf(h[t].z, x4.z, h[t].w * x4.w)));
+                    d = t == 0 ? dt : d + dt;
+                }
+                s[u] = d;
+            }
+            const float r = reduce_chunk<G, U>(s, lane);
+            if (writer) a.g[p + lane] = g_prev + r;
+        }
+        if (SPMM) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                if (tile + t < a.tile1) {   // uniform over the group
+                    if (a.part) {
+                        if (active[t]) st4(a.part + v * a.ldp + c[t], acc[t]);
+                    } else {
+                        finish<G>(a.epi, row, c[t], active[t], acc[t], lane, tile + t);
+                    }
+                }
             }
         }
     }
@@ -688,6 +782,38 @@ int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, in
     return SL_OK;
 }
 
+// Batches above 256 columns take two tiles per pass with half the chunk width (the same number of row
+// gathers in flight per lane).
+template <bool SPMM>
+static void launch_bwd_kernel(int G, int U, int B, int nv, BwdArgs b, hipStream_t s)
+{
+    b.tile0 = 0;
+    b.tile1 = (B + 4 * G - 1) / (4 * G);
+    if (B > 256) {
+        // One launch per pair of tiles: all groups then gather from the same 512 columns at a time (measured
+        // 15 % faster at 1024 columns), and the stream order makes a later pair add to the gradient entries
+        // that the earlier pair stored.  Very short rows (chunks of 2) walk all pairs in one launch instead:
+        // there the second pass over the row pointers costs more than the locality gains.
+        const dim3 grid(groups_to_blocks(nv, 64));
+        const int tiles = b.tile1;
+        if (U < 4) {
+            hipLaunchKernelGGL((bwd_pair_kernel<2, SPMM>), grid, dim3(BLOCK), 0, s, b);
+            return;
+        }
+        for (int t0 = 0; t0 < tiles; t0 += 2) {
+            b.tile0 = t0;
+            b.tile1 = min(t0 + 2, tiles);
+            if (U >= 8) hipLaunchKernelGGL((bwd_pair_kernel<4, SPMM>), grid, dim3(BLOCK), 0, s, b);
+            else hipLaunchKernelGGL((bwd_pair_kernel<2, SPMM>), grid, dim3(BLOCK), 0, s, b);
+        }
+        return;
+    }
+    dispatch_gu(G, U, [&](auto g, auto u) {
+        constexpr int GG = decltype(g)::value, UU = decltype(u)::value;
+        hipLaunchKernelGGL((bwd_kernel<GG, UU, SPMM>), dim3(groups_to_blocks(nv, GG)), dim3(BLOCK), 0, s, b);
+    });
+}
+
 int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, int64_t ldg, int B, float *gx,
                     int64_t ldgx, hipStream_t s)
 {
@@ -721,10 +847,7 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
         }
         {
             ProfScope ps(L, K_BWD_FUSED, s);
-            dispatch_gu(G, U, [&](auto g, auto u) {
-                constexpr int GG = decltype(g)::value, UU = decltype(u)::value;
-                hipLaunchKernelGGL((bwd_kernel<GG, UU, true>), dim3(groups_to_blocks(m.nv, GG)), dim3(BLOCK), 0, s, b);
-            });
+            launch_bwd_kernel<true>(G, U, B, m.nv, b, s);
         }
         if (m.split) launch_fix(L, m, b.epi, G, K_BWD_FIX, s);
         if (P) P->dz_ready = B;
@@ -735,10 +858,7 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
         b.held = L->dz; b.ldh = L->ldz; b.gath = x; b.ldga = ldx;
         b.epi = Epi();
         ProfScope ps(L, K_SDDMM, s);
-        dispatch_gu(G, U, [&](auto g, auto u) {
-            constexpr int GG = decltype(g)::value, UU = decltype(u)::value;
-            hipLaunchKernelGGL((bwd_kernel<GG, UU, false>), dim3(groups_to_blocks(m.nv, GG)), dim3(BLOCK), 0, s, b);
-        });
+        launch_bwd_kernel<false>(G, U, B, m.nv, b, s);
     }
     SL_HIP(L, hipGetLastError());
     return SL_OK;

@@ -92,6 +92,9 @@ def test_init_topology_bit_exact(gpu, oracle, n_in, n_out, nnz):
     (200, 150, 3000, 200, 256, 1, 1, True),       # G = 64 path
     (200, 150, 3000, 300, 512, 1, 0, True),       # two batch tiles of 256 columns, ragged tail
     (200, 150, 3000, 299, 512, 1, 0, False),      # SDDMM-only path, tiles + ragged
+    (200, 150, 3000, 600, 1024, 1, 0, True),      # three batch tiles: a pair, then a single one
+    (200, 150, 3000, 1021, 1024, 1, 1, False),    # four batch tiles, ragged, SDDMM only
+    (6, 2000, 12000, 300, 512, 1, 0, True),       # split CSC side with two batch tiles
     (400, 2, 800, 128, 128, 0, 0, True),          # dense output layer: long rows are split
     (3000, 10, 30000, 80, 128, 0, 0, True),       # dense output layer, rows of 3000
     (6, 2000, 12000, 128, 128, 1, 0, True),       # long columns: the CSC side is split
