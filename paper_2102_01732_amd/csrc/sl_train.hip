@@ -13,6 +13,7 @@
 #include <stdio.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "sl_internal.h"
 
@@ -33,6 +34,34 @@ __device__ __forceinline__ float4 clip4(float4 v, int c, int B)
     v.z = (c + 2 < B) ? v.z : 0.f;
     v.w = (c + 3 < B) ? v.w : 0.f;
     return v;
+}
+
+// Cross-lane moves with the lane pattern in the instruction (ds_swizzle, bit mode: source lane =
+// ((lane & AND) | OR) ^ XOR within each half of 32 lanes): unlike __shfl they need no address register.
+template <int XOR>
+__device__ __forceinline__ float swz_xor(float v)
+{
+    static_assert(XOR >= 1 && XOR <= 16, "partner must stay inside a half-wave");
+    return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), (XOR << 10) | 0x1F));
+}
+// value held by lane K of the caller's group of G lanes; for G = 64 lane 32 + K must hold the same value as lane K
+template <int G, int K>
+__device__ __forceinline__ int swz_bcast(int v)
+{
+    static_assert(K >= 0 && K < G && K < 32, "source lane outside the group");
+    constexpr int keep = G >= 32 ? 0 : (0x1F & ~(G - 1));
+    return __builtin_amdgcn_ds_swizzle(v, (K << 5) | keep);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a constant expression
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_seq(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>()), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_seq(f, std::make_integer_sequence<int, N>());
 }
 
 __device__ __forceinline__ void store_row4(float *row, int c, int B, float4 v)
@@ -307,9 +336,9 @@ struct BwdArgs {
     const int *idx;
     const float *w;
     const float *held;
-    long ldh;
+    int ldh;         // leading dimensions fit 31 bits (checked by the entry points): one 32x32->64 multiply per row address
     const float *gath;
-    long ldga;
+    int ldga;
     float *g;        // per stored entry, in the order of this orientation
     float *part;     // SPMM partial sums [nv][ldp] when the matrix is split, else null
     long ldp;
@@ -319,27 +348,41 @@ struct BwdArgs {
     Epi epi;         // SPMM, not split: what to do with the finished grad_x row
 };
 
+template <int G, int M>
+__device__ __forceinline__ float xor_partner(float v)
+{
+    if constexpr (M <= 16) return swz_xor<M>(v);
+    else return __shfl_xor(v, M, G);
+}
 template <int G, int U>
 __device__ __forceinline__ float reduce_chunk(float (&s)[U], int lane)
 {
     constexpr int LOGU = U == 8 ? 3 : U == 4 ? 2 : 1;
-#pragma unroll
-    for (int m = 0; m < LOGU; ++m) {
+    static_for<LOGU>([&](auto mc) {
+        constexpr int m = decltype(mc)::value;
         const bool up = (lane >> m) & 1;
 #pragma unroll
         for (int t = 0; t < (U >> (m + 1)); ++t) {
             const float lo = s[2 * t], hi = s[2 * t + 1];
             const float send = up ? lo : hi;
             const float keep = up ? hi : lo;
-            s[t] = keep + __shfl_xor(send, 1 << m, G);
+            s[t] = keep + xor_partner<G, (1 << m)>(send);
         }
-    }
+    });
     float r = s[0];
-#pragma unroll
-    for (int m = U; m < G; m <<= 1) r += __shfl_xor(r, m, G);
+    if constexpr (U < G) r += xor_partner<G, U>(r);
+    if constexpr (2 * U < G) r += xor_partner<G, 2 * U>(r);
+    if constexpr (4 * U < G) r += xor_partner<G, 4 * U>(r);
+    if constexpr (8 * U < G) r += xor_partner<G, 8 * U>(r);
+    if constexpr (16 * U < G) r += xor_partner<G, 16 * U>(r);
     return r;
 }
 
+// Index handling: lane u of a group fetches entry u of a chunk (column index and weight, one register
+// each) and the group reads them with cross-lane moves, so the NEXT chunk's indices can be fetched
+// while the current chunk's row gathers are in flight at a cost of two registers.  The gathered
+// operand of the SPMM form is the library's own dz, whose columns past B are zero; the caller's x
+// (gathered by the SDDMM form, held by the SPMM form) may hold anything there and is clipped.
 template <int G, int U, bool SPMM>
 __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
 {
@@ -348,51 +391,59 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
     if (v >= a.nv) return;   // whole groups leave together
     const int p0 = a.vptr[v], p1 = a.vptr[v + 1];
     const long row = a.v2row ? a.v2row[v] : v;
+    const int sub = lane & (U - 1);
     for (int tile = 0; tile * 4 * G < a.B; ++tile) {
         const int c = (tile * G + lane) * 4;
         const bool active = c < a.B;
+        const int cg = active ? c : 0;   // idle lanes gather columns 0..3 and multiply them by a zero h
         float4 h = zero4();
         if (active) {
             h = ld4(a.held + row * a.ldh + c);
             if (a.ragged) h = clip4(h, c, a.B);
         }
         float4 acc = zero4();
+        int my_c = 0;
+        float my_w = 0.f;
+        if (p0 < p1) {
+            const int q = min(p0 + sub, p1 - 1);
+            my_c = a.idx[q];
+            if (SPMM) my_w = a.w[q];
+        }
         for (int p = p0; p < p1; p += U) {
-            int cc[U];
-            float ww[U];
             float4 xv[U];
             float s[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int q = min(p + u, p1 - 1);
-                cc[u] = a.idx[q];
-                if (SPMM) ww[u] = (p + u < p1) ? a.w[q] : 0.f;
-            }
+            // the chunk after this one (clamped to the row's last entry: always a valid position)
+            const int qn = min(p + U + sub, p1 - 1);
+            const int nx_c = a.idx[qn];
+            float nx_w = 0.f;
+            if (SPMM) nx_w = a.w[qn];
             // later batch tiles add to what the earlier ones stored; fetch it with the indices, not after
             // the reduction, so that its latency hides behind the row gathers
             const bool writer = lane < U && p + lane < p1;
             float g_prev = 0.f;
             if (tile > 0 && writer) g_prev = a.g[p + lane];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                xv[u] = zero4();
-                if (active) {
-                    xv[u] = ld4(a.gath + (long)cc[u] * a.ldga + c);
-                    if (a.ragged) xv[u] = clip4(xv[u], c, a.B);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                const int cc = swz_bcast<G, u>(my_c);
+                xv[u] = ld4(a.gath + (long)cc * a.ldga + cg);
+                if (!SPMM && a.ragged) xv[u] = clip4(xv[u], c, a.B);
+            });
+            if (SPMM && p + sub >= p1) my_w = 0.f;   // entries past the end of the row repeat its last one
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
                 if (SPMM) {
-                    acc.x = fmaf(ww[u], xv[u].x, acc.x);
-                    acc.y = fmaf(ww[u], xv[u].y, acc.y);
-                    acc.z = fmaf(ww[u], xv[u].z, acc.z);
-                    acc.w = fmaf(ww[u], xv[u].w, acc.w);
+                    const float w = __int_as_float(swz_bcast<G, u>(__float_as_int(my_w)));
+                    acc.x = fmaf(w, xv[u].x, acc.x);
+                    acc.y = fmaf(w, xv[u].y, acc.y);
+                    acc.z = fmaf(w, xv[u].z, acc.z);
+                    acc.w = fmaf(w, xv[u].w, acc.w);
                 }
                 s[u] = fmaf(h.x, xv[u].x, fmaf(h.y, xv[u].y, fmaf(h.z, xv[u].z, h.w * xv[u].w)));
-            }
+            });
             const float r = reduce_chunk<G, U>(s, lane);
             if (writer) a.g[p + lane] = g_prev + r;
+            my_c = nx_c;
+            my_w = nx_w;
         }
         if (SPMM) {
             if (a.part) {
@@ -403,8 +454,6 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
         }
     }
 }
-
-
 
 // The same walk for batches above 256 columns: a group of 64 lanes carries T = 2 batch tiles (of 256
 // columns) at once and covers the tiles [tile0, tile1) of its launch.  A lane holds two float4 per gathered
@@ -835,7 +884,7 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
         const SegMat &m = L->bwd;
         const int U = chunk_width(m, L->nnz);
         b.vptr = m.vptr; b.v2row = m.v2row; b.nv = m.nv; b.idx = m.idx; b.w = L->valT;
-        b.held = x; b.ldh = ldx; b.gath = L->dz; b.ldga = L->ldz;
+        b.held = x; b.ldh = (int)ldx; b.gath = L->dz; b.ldga = L->ldz;
         if (m.split) b.part = (float *)(L->scratch + L->cp.partial);
         sl_layer *P = gx ? nullptr : L->producer;
         if (P) {   // hand dz straight to the layer that produced x
@@ -855,7 +904,7 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
         const SegMat &m = L->fwd;
         const int U = chunk_width(m, L->nnz);
         b.vptr = m.vptr; b.v2row = m.v2row; b.nv = m.nv; b.idx = m.idx; b.w = nullptr;
-        b.held = L->dz; b.ldh = L->ldz; b.gath = x; b.ldga = ldx;
+        b.held = L->dz; b.ldh = L->ldz; b.gath = x; b.ldga = (int)ldx;
         b.epi = Epi();
         ProfScope ps(L, K_SDDMM, s);
         launch_bwd_kernel<false>(G, U, B, m.nv, b, s);
