@@ -10,7 +10,7 @@
  * exist: no dense matrix and no mask is ever formed.
  *
  * Dense operands (activations, their gradients) are DEVICE pointers to fp32 in feature-major
- * layout: element (neuron i, sample b) at i*ld + b, with ld >= B, ld % 4 == 0 and a 16-byte
+ * layout: element (neuron i, sample b) at i*ld + b, with B <= ld < 2^31, ld % 4 == 0 and a 16-byte
  * aligned base pointer.  Columns b >= B of a row are never written and never influence a result.
  *
  * Ownership: all device memory belongs to the caller.  `state_dev` holds everything that

@@ -249,7 +249,8 @@ int sparse_layer_init(const sl_config *cfg, void *state_dev, size_t state_bytes,
 static int check_dense(sl_layer *L, const void *p, int64_t ld, int B, const char *what)
 {
     if (!p) return set_err(L, SL_EINVAL, "%s is null", what);
-    if (ld < B || (ld & 3)) return set_err(L, SL_EINVAL, "%s: leading dimension %lld must be >= B and a multiple of 4", what, (long long)ld);
+    if (ld < B || (ld & 3) || ld > INT32_MAX)
+        return set_err(L, SL_EINVAL, "%s: leading dimension %lld must be >= B, a multiple of 4 and below 2^31", what, (long long)ld);
     if ((uintptr_t)p & 15) return set_err(L, SL_EINVAL, "%s must be 16-byte aligned", what);
     return SL_OK;
 }

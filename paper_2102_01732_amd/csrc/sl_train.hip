@@ -171,7 +171,7 @@ struct FwdArgs {
     const int *idx;
     const float *w;
     const float *x;
-    long ldx;
+    int ldx;         // fits 31 bits (checked by the entry points)
     float *part;     // partial sums [nv][ldp] when the matrix is split, else null
     long ldp;
     Epi epi;
@@ -469,14 +469,16 @@ __global__ __launch_bounds__(BLOCK) void bwd_pair_kernel(BwdArgs a)
     if (v >= a.nv) return;   // whole groups leave together
     const int p0 = a.vptr[v], p1 = a.vptr[v + 1];
     const long row = a.v2row ? a.v2row[v] : v;
+    const int sub = lane & (U - 1);
     for (int tile = a.tile0; tile < a.tile1; tile += T) {
-        int c[T];
+        int c[T], cg[T];
         bool active[T];
         float4 h[T], acc[T];
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             c[t] = ((tile + t) * G + lane) * 4;
             active[t] = c[t] < a.B;
+            cg[t] = active[t] ? c[t] : 0;   // idle lanes gather columns 0..3 and multiply them by a zero h
             h[t] = zero4();
             if (active[t]) {
                 h[t] = ld4(a.held + row * a.ldh + c[t]);
@@ -484,52 +486,58 @@ __global__ __launch_bounds__(BLOCK) void bwd_pair_kernel(BwdArgs a)
             }
             acc[t] = zero4();
         }
+        int my_c = 0;
+        float my_w = 0.f;
+        if (p0 < p1) {
+            const int q = min(p0 + sub, p1 - 1);
+            my_c = a.idx[q];
+            if (SPMM) my_w = a.w[q];
+        }
         for (int p = p0; p < p1; p += U) {
-            int cc[U];
-            float ww[U];
             float4 xv[U][T];
             float s[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int q = min(p + u, p1 - 1);
-                cc[u] = a.idx[q];
-                if (SPMM) ww[u] = (p + u < p1) ? a.w[q] : 0.f;
-            }
-            // later batch tiles add to what the earlier ones stored; fetch it with the indices, not after
-            // the reduction, so that its latency hides behind the row gathers
+            const int qn = min(p + U + sub, p1 - 1);   // the chunk after this one, clamped to a valid position
+            const int nx_c = a.idx[qn];
+            float nx_w = 0.f;
+            if (SPMM) nx_w = a.w[qn];
+            // later tile pairs add to what the earlier ones stored; fetch it with the indices, not after the
+            // reduction, so that its latency hides behind the row gathers
             const bool writer = lane < U && p + lane < p1;
             float g_prev = 0.f;
             if (tile > 0 && writer) g_prev = a.g[p + lane];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                const float *src = a.gath + (long)swz_bcast<G, u>(my_c) * a.ldga;
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
-                    xv[u][t] = zero4();
-                    if (active[t]) {
-                        xv[u][t] = ld4(a.gath + (long)cc[u] * a.ldga + c[t]);
-                        if (a.ragged) xv[u][t] = clip4(xv[u][t], c[t], a.B);
-                    }
+                    xv[u][t] = ld4(src + cg[t]);
+                    if (!SPMM && a.ragged) xv[u][t] = clip4(xv[u][t], c[t], a.B);
                 }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
+            });
+            if (SPMM && p + sub >= p1) my_w = 0.f;   // entries past the end of the row repeat its last one
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                float w = 0.f;
+                if (SPMM) w = __int_as_float(swz_bcast<G, u>(__float_as_int(my_w)));
                 float d = 0.f;
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
                     const float4 x4 = xv[u][t];
                     if (SPMM) {
-                        acc[t].x = fmaf(ww[u], x4.x, acc[t].x);
-                        acc[t].y = fmaf(ww[u], x4.y, acc[t].y);
-                        acc[t].z = fmaf(ww[u], x4.z, acc[t].z);
-                        acc[t].w = fmaf(ww[u], x4.w, acc[t].w);
+                        acc[t].x = fmaf(w, x4.x, acc[t].x);
+                        acc[t].y = fmaf(w, x4.y, acc[t].y);
+                        acc[t].z = fmaf(w, x4.z, acc[t].z);
+                        acc[t].w = fmaf(w, x4.w, acc[t].w);
                     }
                     const float dt = fmaf(h[t].x, x4.x, fmaf(h[t].y, x4.y, fmaf(h[t].z, x4.z, h[t].w * x4.w)));
                     d = t == 0 ? dt : d + dt;
                 }
                 s[u] = d;
-            }
+            });
             const float r = reduce_chunk<G, U>(s, lane);
             if (writer) a.g[p + lane] = g_prev + r;
+            my_c = nx_c;
+            my_w = nx_w;
         }
         if (SPMM) {
 #pragma unroll
@@ -804,7 +812,7 @@ int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, in
     const int G = group_width(B), U = chunk_width(m, L->nnz);
     const int tiles = (B + 4 * G - 1) / (4 * G);
     FwdArgs f;
-    f.vptr = m.vptr; f.v2row = m.v2row; f.nv = m.nv; f.idx = m.idx; f.w = L->val; f.x = x; f.ldx = ldx;
+    f.vptr = m.vptr; f.v2row = m.v2row; f.nv = m.nv; f.idx = m.idx; f.w = L->val; f.x = x; f.ldx = (int)ldx;
     f.part = m.split ? (float *)(L->scratch + L->cp.partial) : nullptr; f.ldp = L->ldz;
     Epi &e = f.epi;
     e.mode = EPI_FWD; e.out = a; e.ldo = lda; e.bias = L->bias; e.mask_w = save_sign ? L->mask : nullptr; e.mask_r = nullptr; e.ldm = L->ldm;
