@@ -36,21 +36,38 @@ __device__ __forceinline__ float4 clip4(float4 v, int c, int B)
     return v;
 }
 
-// Cross-lane moves with the lane pattern in the instruction (ds_swizzle, bit mode: source lane =
-// ((lane & AND) | OR) ^ XOR within each half of 32 lanes): unlike __shfl they need no address register.
-template <int XOR>
-__device__ __forceinline__ float swz_xor(float v)
+// Cross-lane moves whose lane pattern sits in the instruction, so that none needs an address register.
+// DPP forms (dpp_ctrl: quad_perm 0x00-0xFF, row_shl:n 0x100+n, row_shr:n 0x110+n, row_ror:n 0x120+n,
+// row_newbcast:n 0x150+n; a row is 16 lanes) run in the vector ALU; ds_swizzle (bit mode: source lane =
+// ((lane & AND) | OR) ^ XOR within each half of 32 lanes) takes a trip through the LDS crossbar.
+template <int CTRL, int BANKS>
+__device__ __forceinline__ int dpp_mov(int old, int v)
 {
-    static_assert(XOR >= 1 && XOR <= 16, "partner must stay inside a half-wave");
-    return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), (XOR << 10) | 0x1F));
+    return __builtin_amdgcn_update_dpp(old, v, CTRL, 0xF, BANKS, false);
 }
-// value held by lane K of the caller's group of G lanes; for G = 64 lane 32 + K must hold the same value as lane K
-template <int G, int K>
-__device__ __forceinline__ int swz_bcast(int v)
+// value of lane (lane ^ XOR); the partner is inside the caller's group for every use below
+template <int G, int XOR>
+__device__ __forceinline__ float xor_partner(float v)
 {
-    static_assert(K >= 0 && K < G && K < 32, "source lane outside the group");
-    constexpr int keep = G >= 32 ? 0 : (0x1F & ~(G - 1));
-    return __builtin_amdgcn_ds_swizzle(v, (K << 5) | keep);
+    static_assert(XOR >= 1 && XOR < G && (XOR & (XOR - 1)) == 0, "partner outside the group");
+    const int i = __float_as_int(v);
+    if constexpr (XOR == 1) return __int_as_float(dpp_mov<0xB1, 0xF>(i, i));        // quad_perm [1,0,3,2]
+    else if constexpr (XOR == 2) return __int_as_float(dpp_mov<0x4E, 0xF>(i, i));   // quad_perm [2,3,0,1]
+    else if constexpr (XOR == 4) {
+        const int t = dpp_mov<0x104, 0x5>(i, i);             // lanes 0-3, 8-11 of a row read lane + 4
+        return __int_as_float(dpp_mov<0x114, 0xA>(t, i));    // lanes 4-7, 12-15 read lane - 4
+    } else if constexpr (XOR == 8) return __int_as_float(dpp_mov<0x128, 0xF>(i, i));   // row_ror:8
+    else if constexpr (XOR == 16) return __int_as_float(__builtin_amdgcn_ds_swizzle(i, (16 << 10) | 0x1F));
+    else return __shfl_xor(v, XOR, G);
+}
+// Value of entry K of a chunk, which every lane with (lane & (U - 1)) == K holds (U <= 8 <= K's row of 16
+// lanes): lane K of the caller's row for groups of 16 lanes or more, lane K of the group of 8 otherwise.
+template <int G, int K>
+__device__ __forceinline__ int chunk_entry(int v)
+{
+    static_assert(K >= 0 && K < 8, "chunks have at most eight entries");
+    if constexpr (G >= 16) return dpp_mov<0x150 + K, 0xF>(v, v);
+    else return __builtin_amdgcn_ds_swizzle(v, (K << 5) | 0x18);
 }
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a constant expression
 template <typename F, int... I>
@@ -348,12 +365,6 @@ struct BwdArgs {
     Epi epi;         // SPMM, not split: what to do with the finished grad_x row
 };
 
-template <int G, int M>
-__device__ __forceinline__ float xor_partner(float v)
-{
-    if constexpr (M <= 16) return swz_xor<M>(v);
-    else return __shfl_xor(v, M, G);
-}
 template <int G, int U>
 __device__ __forceinline__ float reduce_chunk(float (&s)[U], int lane)
 {
@@ -424,7 +435,7 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
             if (tile > 0 && writer) g_prev = a.g[p + lane];
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
-                const int cc = swz_bcast<G, u>(my_c);
+                const int cc = chunk_entry<G, u>(my_c);
                 xv[u] = ld4(a.gath + (long)cc * a.ldga + cg);
                 if (!SPMM && a.ragged) xv[u] = clip4(xv[u], c, a.B);
             });
@@ -432,7 +443,7 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
                 if (SPMM) {
-                    const float w = __int_as_float(swz_bcast<G, u>(__float_as_int(my_w)));
+                    const float w = __int_as_float(chunk_entry<G, u>(__float_as_int(my_w)));
                     acc.x = fmaf(w, xv[u].x, acc.x);
                     acc.y = fmaf(w, xv[u].y, acc.y);
                     acc.z = fmaf(w, xv[u].z, acc.z);
@@ -507,7 +518,7 @@ __global__ __launch_bounds__(BLOCK) void bwd_pair_kernel(BwdArgs a)
             if (tile > 0 && writer) g_prev = a.g[p + lane];
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
-                const float *src = a.gath + (long)swz_bcast<G, u>(my_c) * a.ldga;
+                const float *src = a.gath + (long)chunk_entry<G, u>(my_c) * a.ldga;
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
                     xv[u][t] = ld4(src + cg[t]);
@@ -518,7 +529,7 @@ __global__ __launch_bounds__(BLOCK) void bwd_pair_kernel(BwdArgs a)
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
                 float w = 0.f;
-                if (SPMM) w = __int_as_float(swz_bcast<G, u>(__float_as_int(my_w)));
+                if (SPMM) w = __int_as_float(chunk_entry<G, u>(__float_as_int(my_w)));
                 float d = 0.f;
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
