@@ -226,6 +226,19 @@ def main():
                    sample=f"one training step (forward, loss, backward, update) on the first {ns} samples of "
                           f"minibatch 0 at the full layer shapes; {c1 - c0:.1f} s; evolution not included")
 
+    # ---- forward only (inference): the whole network on every minibatch block, no sign masks kept
+    def time_inference(model, xs, b, reps):
+        model.infer(xs[0], b, model.acts)
+        torch.cuda.synchronize()
+        q0 = time.perf_counter()
+        for r in range(reps):
+            model.infer(xs[r % len(xs)], b, model.acts)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - q0
+        return dict(batch=b, batches=reps, samples_per_s=reps * b / dt, ms_per_batch=dt / reps * 1e3)
+
+    inference = [time_inference(net, blocks, B, n_blocks)]
+
     # ---- sparse averaging of two replicas (eq. 2 + magnitude re-pruning) of the first 10^6 x 10^6 layer
     average = None
     if len(net.layers) > 1:
@@ -261,7 +274,18 @@ def main():
     net.close()
     del net, blocks, labels
     torch.cuda.empty_cache()
-    for name in [n for n in args.extra_workloads.split(",") if n in wl.WORKLOADS and n != args.workload]:
+    extra = [n for n in args.extra_workloads.split(",") if n in wl.WORKLOADS and n != args.workload]
+    if extra:
+        # the same network sized for minibatches of 1024 samples (batch tiles of 256 columns in the forward kernel)
+        wide = binding.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=1024)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed + 7)
+        xs = [torch.randn((n_in, 1024), generator=gen, device=dev) for _ in range(2)]
+        inference.append(time_inference(wide, xs, 1024, 16))
+        wide.close()
+        del wide, xs
+        torch.cuda.empty_cache()
+    for name in extra:
         others.append(run_small(name, torch, np, binding, wl, dev, not args.no_cpu_baseline))
 
     out = dict(metric="sparse-MLP train samples/s", value=value, unit="samples/s", n_gpus=1, steps=K,
@@ -271,7 +295,7 @@ def main():
                            nnz=[s.nnz for s in w.layers], alpha=w.alpha, zeta=w.zeta,
                            evolutions_in_timed_region=K // n_blocks, parallelism="single GPU"),
                roofline=roofline, cpu_baseline=cpu, evolve_ms_all_layers=evolve_ms, kernels=kernels[:12],
-               importance_pruning=importance, sparse_average=average, other_workloads=others)
+               inference=inference, importance_pruning=importance, sparse_average=average, other_workloads=others)
     print(json.dumps(out))
 
 

@@ -104,9 +104,19 @@ def test_init_topology_bit_exact(gpu, oracle, n_in, n_out, nnz):
     (2000, 3001, 6000, 30, 32, 1, 1, False),      # span SDDMM, G = 8, ragged batch
     (1500, 2500, 5000, 300, 512, 1, 0, True)])    # span kernels with two batch tiles
 def test_forward_backward_update_one_layer(gpu, oracle, n_in, n_out, nnz, B, max_batch, act_kind, parity, need_gx):
+    run_one_layer(gpu, oracle, n_in, n_out, nnz, B, max_batch, act_kind, parity, need_gx)
+
+
+@pytest.mark.parametrize("alpha,parity", [(0.0, 0), (0.0, 1), (0.05, 1), (0.75, 0)])
+def test_other_slopes_including_plain_relu(gpu, oracle, alpha, parity):
+    """alpha = 0 is ReLU (the comparison activation of the experiments); 0.05 and 0.75 are slopes their tables use."""
+    run_one_layer(gpu, oracle, 500, 400, 9000, 128, 128, 1, parity, True, alpha=alpha)
+
+
+def run_one_layer(gpu, oracle, n_in, n_out, nnz, B, max_batch, act_kind, parity, need_gx, alpha=0.6):
     import torch
     G, O = make_pair(gpu, oracle, n_in, n_out, nnz, act_kind=act_kind, parity=parity, max_batch=max_batch,
-                     need_input_grad=need_gx, limit=0.2)
+                     need_input_grad=need_gx, limit=0.2, alpha=alpha)
     assert_same_topology(G, O)
     rng = np.random.default_rng(n_in + B)
     # non-zero bias and velocity so that every term of the formulas is exercised
