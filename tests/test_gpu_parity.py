@@ -102,7 +102,8 @@ def test_init_topology_bit_exact(gpu, oracle, n_in, n_out, nnz):
     (2000, 3000, 90000, 128, 128, 1, 0, True),
     (2000, 3001, 6000, 128, 128, 1, 0, True),     # rows of about two entries: span kernels, ragged last span
     (2000, 3001, 6000, 30, 32, 1, 1, False),      # span SDDMM, G = 8, ragged batch
-    (1500, 2500, 5000, 300, 512, 1, 0, True)])    # span kernels with two batch tiles
+    (1500, 2500, 5000, 300, 512, 1, 0, True),     # span kernels with two batch tiles
+    (1500, 2500, 5000, 1000, 1024, 1, 1, True)])  # very short rows, four tiles: both tile pairs walked in one launch
 def test_forward_backward_update_one_layer(gpu, oracle, n_in, n_out, nnz, B, max_batch, act_kind, parity, need_gx):
     run_one_layer(gpu, oracle, n_in, n_out, nnz, B, max_batch, act_kind, parity, need_gx)
 
