@@ -631,33 +631,9 @@ __global__ __launch_bounds__(BLOCK) void fwd_span_kernel(FwdArgs a)
 // With a CSC view the master copy is in CSC order and the CSR copy read by forward is refreshed
 // through csr_pos.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void update_kernel(long n, float *w, float *vel, const float *g, float lr,
-                                                      float mu, float wd, const int *scatter_pos, float *w_csr,
-                                                      int nb, float *bias, float *bias_vel, const float *gbias)
-{
-#pragma clang fp contract(off)   // separate roundings: this must equal the plain fp32 evaluation
-    const long t = (long)blockIdx.x * BLOCK + threadIdx.x;
-    if (t < n) {
-        const float wt = w[t];
-        const float gg = g[t] + wd * wt;
-        const float vn = mu * vel[t] - lr * gg;
-        const float wn = wt + vn;
-        vel[t] = vn;
-        w[t] = wn;
-        if (scatter_pos) w_csr[scatter_pos[t]] = wn;
-    } else if (t - n < nb) {
-        const long j = t - n;
-        const float vn = mu * bias_vel[j] - lr * gbias[j];
-        bias_vel[j] = vn;
-        bias[j] = bias[j] + vn;
-    }
-}
-
-// The same update for up to MAX_MULTI layers in ONE launch (small networks are bound by the number
-// of dependent launches per step, not by bandwidth).
 struct UpdateOne {
     long n;          // stored connections
-    long first;      // first global thread index of this layer
+    long first;      // first global thread index of this layer (update_many_kernel)
     float *w, *vel;
     const float *g;
     const int *scatter_pos;
@@ -667,32 +643,73 @@ struct UpdateOne {
     const float *gbias;
     float lr, mu, wd;
 };
+__device__ __forceinline__ void update_one(float &w, float &vel, float g, float lr, float mu, float wd)
+{
+#pragma clang fp contract(off)   // separate roundings: this must equal the plain fp32 evaluation
+    const float gg = g + wd * w;
+    const float vn = mu * vel - lr * gg;
+    vel = vn;
+    w = w + vn;
+}
+// Thread t of a layer takes the four connections 4t .. 4t+3 (16-byte loads and stores of the three streams;
+// the state arrays are 256-byte aligned), the threads after ceil(n/4) take one bias each.
+__device__ __forceinline__ void update_thread(const UpdateOne &u, long t)
+{
+#pragma clang fp contract(off)
+    const long quads = (u.n + 3) / 4;
+    if (t < quads) {
+        const long e = 4 * t;
+        if (e + 3 < u.n) {
+            float4 w = ld4(u.w + e), v = ld4(u.vel + e);
+            const float4 g = ld4(u.g + e);
+            update_one(w.x, v.x, g.x, u.lr, u.mu, u.wd);
+            update_one(w.y, v.y, g.y, u.lr, u.mu, u.wd);
+            update_one(w.z, v.z, g.z, u.lr, u.mu, u.wd);
+            update_one(w.w, v.w, g.w, u.lr, u.mu, u.wd);
+            st4(u.vel + e, v);
+            st4(u.w + e, w);
+            if (u.scatter_pos) {
+                const int4 pos = *reinterpret_cast<const int4 *>(u.scatter_pos + e);
+                u.w_csr[pos.x] = w.x;
+                u.w_csr[pos.y] = w.y;
+                u.w_csr[pos.z] = w.z;
+                u.w_csr[pos.w] = w.w;
+            }
+        } else {
+            for (long i = e; i < u.n; ++i) {
+                float w = u.w[i], v = u.vel[i];
+                update_one(w, v, u.g[i], u.lr, u.mu, u.wd);
+                u.vel[i] = v;
+                u.w[i] = w;
+                if (u.scatter_pos) u.w_csr[u.scatter_pos[i]] = w;
+            }
+        }
+    } else if (t - quads < u.nb) {
+        const long j = t - quads;
+        const float vn = u.mu * u.bias_vel[j] - u.lr * u.gbias[j];
+        u.bias_vel[j] = vn;
+        u.bias[j] = u.bias[j] + vn;
+    }
+}
+static long update_threads(long n, int nb) { return (n + 3) / 4 + nb; }
+
+__global__ __launch_bounds__(BLOCK) void update_kernel(UpdateOne u)
+{
+    update_thread(u, (long)blockIdx.x * BLOCK + threadIdx.x);
+}
+
+// The same update for up to MAX_MULTI layers in ONE launch (small networks are bound by the number
+// of dependent launches per step, not by bandwidth).
 struct UpdateMany {
     int count;
     UpdateOne l[MAX_MULTI];
 };
 __global__ __launch_bounds__(BLOCK) void update_many_kernel(UpdateMany a)
 {
-#pragma clang fp contract(off)
     const long gt = (long)blockIdx.x * BLOCK + threadIdx.x;
     int k = 0;
     while (k + 1 < a.count && gt >= a.l[k + 1].first) ++k;
-    const UpdateOne &u = a.l[k];
-    const long t = gt - u.first;
-    if (t < u.n) {
-        const float wt = u.w[t];
-        const float gg = u.g[t] + u.wd * wt;
-        const float vn = u.mu * u.vel[t] - u.lr * gg;
-        const float wn = wt + vn;
-        u.vel[t] = vn;
-        u.w[t] = wn;
-        if (u.scatter_pos) u.w_csr[u.scatter_pos[t]] = wn;
-    } else if (t - u.n < u.nb) {
-        const long j = t - u.n;
-        const float vn = u.mu * u.bias_vel[j] - u.lr * u.gbias[j];
-        u.bias_vel[j] = vn;
-        u.bias[j] = u.bias[j] + vn;
-    }
+    update_thread(a.l[k], gt - a.l[k].first);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -932,21 +949,23 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
     return SL_OK;
 }
 
+static UpdateOne update_args(const sl_layer *L)
+{
+    UpdateOne u;
+    u.n = L->nnz; u.first = 0; u.nb = (int)L->cfg.n_out;
+    u.w = L->has_csc ? L->valT : L->val; u.vel = L->has_csc ? L->velT : L->vel; u.g = L->grad;
+    u.scatter_pos = L->has_csc ? L->csr_pos : nullptr; u.w_csr = L->has_csc ? L->val : nullptr;
+    u.bias = L->bias; u.bias_vel = L->bias_vel; u.gbias = L->grad_bias;
+    u.lr = L->cfg.lr; u.mu = L->cfg.momentum; u.wd = L->cfg.weight_decay;
+    return u;
+}
+
 int launch_update(sl_layer *L, hipStream_t s)
 {
-    const long n = L->nnz;
-    const int nb = (int)L->cfg.n_out;
-    const long total = n + nb;
-    dim3 grid((unsigned)((total + BLOCK - 1) / BLOCK));
+    const UpdateOne u = update_args(L);
+    const long total = update_threads(u.n, u.nb);
     ProfScope ps(L, K_UPDATE, s);
-    if (L->has_csc)
-        hipLaunchKernelGGL(update_kernel, grid, dim3(BLOCK), 0, s, n, L->valT, L->velT, L->grad, L->cfg.lr,
-                           L->cfg.momentum, L->cfg.weight_decay, L->csr_pos, L->val, nb, L->bias, L->bias_vel,
-                           L->grad_bias);
-    else
-        hipLaunchKernelGGL(update_kernel, grid, dim3(BLOCK), 0, s, n, L->val, L->vel, L->grad, L->cfg.lr,
-                           L->cfg.momentum, L->cfg.weight_decay, (const int *)nullptr, (float *)nullptr, nb, L->bias,
-                           L->bias_vel, L->grad_bias);
+    hipLaunchKernelGGL(update_kernel, dim3((unsigned)((total + BLOCK - 1) / BLOCK)), dim3(BLOCK), 0, s, u);
     SL_HIP(L, hipGetLastError());
     return SL_OK;
 }
@@ -964,15 +983,10 @@ int launch_update_many(sl_layer *const *layers, int count, hipStream_t s)
     a.count = count;
     long first = 0;
     for (int k = 0; k < count; ++k) {
-        sl_layer *L = layers[k];
-        UpdateOne &u = a.l[k];
-        u.n = L->nnz; u.first = first; u.nb = (int)L->cfg.n_out;
-        u.w = L->has_csc ? L->valT : L->val; u.vel = L->has_csc ? L->velT : L->vel; u.g = L->grad;
-        u.scatter_pos = L->has_csc ? L->csr_pos : nullptr; u.w_csr = L->has_csc ? L->val : nullptr;
-        u.bias = L->bias; u.bias_vel = L->bias_vel; u.gbias = L->grad_bias;
-        u.lr = L->cfg.lr; u.mu = L->cfg.momentum; u.wd = L->cfg.weight_decay;
+        a.l[k] = update_args(layers[k]);
+        a.l[k].first = first;
         // every layer starts on a block boundary so that a block never straddles two layers
-        first += ((u.n + u.nb + BLOCK - 1) / BLOCK) * BLOCK;
+        first += ((update_threads(a.l[k].n, a.l[k].nb) + BLOCK - 1) / BLOCK) * BLOCK;
     }
     ProfScope ps(layers[0], K_UPDATE, s);
     hipLaunchKernelGGL(update_many_kernel, dim3((unsigned)(first / BLOCK)), dim3(BLOCK), 0, s, a);
