@@ -189,6 +189,7 @@ struct FwdArgs {
     const float *w;
     const float *x;
     int ldx;         // fits 31 bits (checked by the entry points)
+    int twin_rows;   // > 0: fully dense matrix of this many rows, each cut into nv / twin_rows equal runs (see fwd_kernel)
     float *part;     // partial sums [nv][ldp] when the matrix is split, else null
     long ldp;
     Epi epi;
@@ -198,9 +199,13 @@ template <int G, int U>
 __global__ __launch_bounds__(BLOCK) void fwd_kernel(FwdArgs a)
 {
     const int lane = threadIdx.x % G;
-    const long v = (long)blockIdx.x * (BLOCK / G) + threadIdx.x / G;
+    long v = (long)blockIdx.x * (BLOCK / G) + threadIdx.x / G;
     const int c = (blockIdx.y * G + lane) * 4;
     if (v >= a.nv || c >= a.epi.B) return;
+    // Fully dense narrow matrices (the output layers): neighbouring groups take the SAME run of columns of
+    // neighbouring rows, so the groups of a wavefront and of a block gather the same operand rows at the same
+    // time and all but the first are served by the CU's cache instead of by memory.
+    if (a.twin_rows > 0) v = (v % a.twin_rows) * (a.nv / a.twin_rows) + v / a.twin_rows;
     const int p0 = a.vptr[v], p1 = a.vptr[v + 1];
     const float *xb = a.x + c;
     float4 acc = zero4();
@@ -841,6 +846,9 @@ int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, in
     const int tiles = (B + 4 * G - 1) / (4 * G);
     FwdArgs f;
     f.vptr = m.vptr; f.v2row = m.v2row; f.nv = m.nv; f.idx = m.idx; f.w = L->val; f.x = x; f.ldx = (int)ldx;
+    // every row of a fully dense matrix has the same length, hence the same number of equal runs
+    const bool dense = m.split && L->nnz == L->cfg.n_in * L->cfg.n_out && m.nv % m.n_rows == 0;
+    f.twin_rows = dense && m.n_rows > 1 ? m.n_rows : 0;
     f.part = m.split ? (float *)(L->scratch + L->cp.partial) : nullptr; f.ldp = L->ldz;
     Epi &e = f.epi;
     e.mode = EPI_FWD; e.out = a; e.ldo = lda; e.bias = L->bias; e.mask_w = save_sign ? L->mask : nullptr; e.mask_r = nullptr; e.ldm = L->ldm;
