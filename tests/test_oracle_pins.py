@@ -171,8 +171,12 @@ def dense_reference(L, x, grad_a):
     (30, 20, 8, 4, 1, 0),                                                   # many empty rows and columns
     (5, 1, 3, 1, 1, 1), (64, 48, 700, 17, 1, 0)])
 def test_forward_backward_against_dense_matrices(oracle, n_in, n_out, nnz, B, act_kind, parity):
-    L = make_layer(oracle, n_in, n_out, nnz, act_kind, parity, alpha=0.6, seed=21)
-    rng = np.random.default_rng(1)
+    check_against_dense(oracle, n_in, n_out, nnz, B, act_kind, parity, 0.6, 21)
+
+
+def check_against_dense(oracle, n_in, n_out, nnz, B, act_kind, parity, alpha, seed):
+    L = make_layer(oracle, n_in, n_out, nnz, act_kind, parity, alpha=alpha, seed=seed)
+    rng = np.random.default_rng(seed + 1)
     L.bias = rng.standard_normal(n_out).astype(np.float32)
     x = rng.standard_normal((n_in, B)).astype(np.float32)
     ga = rng.standard_normal((n_out, B)).astype(np.float32)
@@ -303,9 +307,12 @@ def test_momentum_update_matches_two_term_recurrence_and_closed_form(oracle):
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("n_in,n_out,nnz", [(60, 40, 500), (20, 10, 120), (9, 4, 36)])
 def test_evolve_invariants(oracle, mode, n_in, n_out, nnz):
-    zeta = 0.3
-    L = make_layer(oracle, n_in, n_out, nnz, prune_mode=mode, seed=13)
-    rng = np.random.default_rng(4)
+    check_evolve(oracle, mode, n_in, n_out, nnz, 0.3, 13)
+
+
+def check_evolve(oracle, mode, n_in, n_out, nnz, zeta, seed):
+    L = make_layer(oracle, n_in, n_out, nnz, prune_mode=mode, seed=seed)
+    rng = np.random.default_rng(seed + 4)
     L.vel = rng.standard_normal(nnz).astype(np.float32)
     flat0, val0, vel0 = L.flat().copy(), L.val.copy(), L.vel.copy()
     remove = L.prune_flags(zeta)
@@ -324,7 +331,8 @@ def test_evolve_invariants(oracle, mode, n_in, n_out, nnz):
             kk = int(np.floor(zeta * idx.size + 0.5))
             order = idx[np.lexsort((flat0[idx], np.abs(val0[idx])))]
             assert np.array_equal(np.sort(order[:kk]), np.flatnonzero(remove & sel))
-    assert np.abs(val0[remove]).max() <= np.abs(val0[~remove]).min() or mode == 1
+    if mode == 0 and remove.any() and not remove.all():
+        assert np.abs(val0[remove]).max() <= np.abs(val0[~remove]).min()
     flat1 = L.flat()
     assert np.all(np.diff(flat1.astype(np.int64)) > 0)                       # no duplicates, rows sorted
     # survivors keep weight and velocity bit for bit
@@ -535,3 +543,27 @@ def test_retain_valid_updates_against_dense_masking(oracle):
     L.update()
     changed = L.val != w_before
     assert np.array_equal(changed, L.grad_val != 0)         # brand-new connections are left alone (zero velocity)
+
+
+# ---------------------------------------------------------------------------- randomly drawn tiny layers
+def test_random_tiny_layers_against_dense_matrices_and_set_invariants(oracle):
+    """The fixed cases above, re-run on shapes, densities, slopes and fractions drawn by hypothesis
+    (empty layers, single rows and columns, fully dense layers and zeta = 0 or 1 included)."""
+    hyp = pytest.importorskip("hypothesis")
+    st = hyp.strategies
+
+    @hyp.settings(max_examples=60, deadline=None, derandomize=True)
+    @hyp.given(st.integers(1, 14), st.integers(1, 11), st.floats(0.0, 1.0), st.integers(1, 6), st.integers(0, 1),
+               st.integers(0, 1), st.sampled_from([0.0, 0.05, 0.6, 0.75]), st.sampled_from([0.0, 0.1, 0.3, 0.5, 1.0]),
+               st.integers(0, 1), st.integers(1, 10 ** 6))
+    def run(n_in, n_out, density, B, act_kind, parity, alpha, zeta, mode, seed):
+        nnz = int(round(density * n_in * n_out))
+        check_against_dense(oracle, n_in, n_out, nnz, B, act_kind, parity, alpha, seed)
+        seen["layers"] += 1
+        if nnz > 0:
+            check_evolve(oracle, mode, n_in, n_out, nnz, zeta, seed)
+            seen["evolved"] += 1
+
+    seen = {"layers": 0, "evolved": 0}
+    run()
+    assert seen["layers"] >= 50 and seen["evolved"] >= 30
