@@ -114,6 +114,30 @@ def test_other_slopes_including_plain_relu(gpu, oracle, alpha, parity):
     run_one_layer(gpu, oracle, 500, 400, 9000, 128, 128, 1, parity, True, alpha=alpha)
 
 
+def test_randomly_drawn_small_layers(gpu, oracle):
+    """Forty small layers with shapes, densities, batch sizes and modes drawn from a seeded generator: single
+    rows and columns, one-sample batches, fully dense and nearly empty patterns, every group width."""
+    rng = np.random.default_rng(20210201)
+    for case in range(40):
+        n_in, n_out = int(rng.integers(1, 90)), int(rng.integers(1, 90))
+        nnz = max(1, int(round(float(rng.choice([0.01, 0.05, 0.2, 0.6, 1.0])) * n_in * n_out)))
+        B = int(rng.choice([1, 2, 3, 4, 7, 32, 33, 64, 100, 128, 130, 256, 300]))
+        max_batch = B + int(rng.choice([0, 0, 5, 64]))
+        act_kind, parity, need_gx = int(rng.integers(0, 2)), int(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        alpha = float(rng.choice([0.0, 0.6, 0.75]))
+        print(f"case {case}: {n_in}x{n_out} nnz={nnz} B={B} max_batch={max_batch} act={act_kind}/{parity} gx={need_gx} "
+              f"alpha={alpha}", flush=True)
+        run_one_layer(gpu, oracle, n_in, n_out, nnz, B, max_batch, act_kind, parity, need_gx, alpha=alpha)
+        mode = int(rng.integers(0, 2))
+        G, O = make_pair(gpu, oracle, n_in, n_out, nnz, prune_mode=mode, need_input_grad=need_gx, seed=100 + case,
+                         max_batch=max_batch)
+        for gen, zeta in ((1, 0.3), (2, float(rng.choice([0.0, 0.5, 1.0])))):
+            O.evolve(zeta, gen)
+            G.evolve(zeta, gen)
+            assert_same_topology(G, O)
+        G.close()
+
+
 def run_one_layer(gpu, oracle, n_in, n_out, nnz, B, max_batch, act_kind, parity, need_gx, alpha=0.6):
     import torch
     G, O = make_pair(gpu, oracle, n_in, n_out, nnz, act_kind=act_kind, parity=parity, max_batch=max_batch,
