@@ -323,9 +323,10 @@ class SparseMLP:
             xin = x if li == 0 else self.acts[li - 1]
             self.layers[li].backward(xin, self.grad_out if li == last else None, B, None)
 
-    def train_step(self, x: torch.Tensor, y: torch.Tensor, B: int):
+    def train_step(self, x: torch.Tensor, y: torch.Tensor, B: int, before_update=None):
         """x [n_in][ld>=B] feature-major, y int32 [B].  Forward, loss written into the output layer,
-        chained backward, one update launch for all layers."""
+        chained backward, one update launch for all layers.  `before_update(self)`, if given, runs between
+        the backward pass and the update (the gradients can be read with SparseLayer.export_grad there)."""
         if self.dropout > 0.0:
             for layer in self.layers[:-1]:
                 layer.set_dropout(self.dropout, self.step_index)
@@ -337,6 +338,8 @@ class SparseMLP:
         n = len(self.layers)
         for li in range(n - 1, -1, -1):
             self.layers[li].backward(x if li == 0 else self.acts[li - 1], None, B, None)
+        if before_update is not None:
+            before_update(self)
         last._check(lib().sparse_layers_update(self._handles, n, _stream()), "sparse_layers_update")
 
     def evolve(self, zeta: float, generation: int):

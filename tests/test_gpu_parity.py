@@ -2,6 +2,8 @@
 the same seeded inputs.  Topology, indices and counts must be bit-exact; fp32 tensors must agree
 within relative 1e-4 after one step and 1e-3 after an epoch (normwise, and max-abs relative to the
 largest oracle magnitude)."""
+import os
+
 import numpy as np
 import pytest
 import scipy.sparse as sp
@@ -366,6 +368,138 @@ def run_network(gpu, oracle, w, n_steps, tol_first=1e-4, tol_end=1e-3, dropout=0
             except AssertionError as e:      # try the next valid branch assignment
                 last_error = e if last_error is None else last_error
     raise last_error
+
+
+def run_network_stepwise(gpu, oracle, w, n_steps, tol_end=1e-3):
+    """A whole epoch on networks too large for the enumeration above (hundreds of pre-activations come within
+    rounding distance of the kink over hundreds of steps, and a single one that takes the other branch grows into
+    a difference of 1e-3 within a few hundred steps).  The GPU trains freely; the oracle follows minibatch by
+    minibatch.  A pre-activation z_jb is ON THE KINK when |z_jb| is below the worst-case rounding error of an
+    fp32 sum of its terms, (n_j + 2) 2^-24 (|b_j| + sum_i |w_ji||x_ib|): there either branch of eq. (3) is a
+    correct result.  Which branch the GPU took shows in its gradient of that step: the other branch changes
+    dz_jb and with it the gradient of row j by u = (dz'_jb - dz_jb) x_b, and the GPU took it if its gradient of
+    that row sits nearer to the oracle's + u than to the oracle's: t = <g_gpu - g_oracle, u> / <u, u> > 1/2
+    (t is about 0 or about 1).  The oracle then re-takes the step with those branches and continues.  Every
+    number compared comes from the oracle; the GPU only selects which of the valid references it is compared
+    with, and a branch missed here can only make the comparison at the end fail."""
+    import torch
+    X, y = wl.dataset(w, n_steps * w.batch)
+    blocks = wl.to_batch_blocks(X, w.batch)
+    net = gpu.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=w.batch)
+    xd, yd = dev(torch, blocks), dev(torch, y)
+    olayers = [oracle.OracleLayer(s.n_in, s.n_out, s.nnz, s.act_kind, s.act_parity, w.alpha, s.init_limit, w.lr,
+                                  w.momentum, 0.0, w.seed, s.layer_id) for s in w.layers]
+    onet = oracle.OracleMLP(olayers)
+    state = {"flips": (), "seen": [], "collect": True}
+
+    def hook(li, layer, a):
+        if not layer.act_kind:
+            return a
+        if state["collect"]:
+            x_in = np.abs(onet.acts[-1]).astype(np.float64)
+            n_j = np.diff(layer.rowptr).astype(np.float64)
+            rows = np.repeat(np.arange(layer.n_out), np.diff(layer.rowptr))
+            absw = np.bincount(rows, weights=np.abs(layer.val).astype(np.float64), minlength=layer.n_out)
+            loose = (n_j + 2.0) * 2.0 ** -24 * (np.abs(layer.bias) + absw * x_in.max())     # >= the bound of any sample
+            for j, b in np.argwhere(np.abs(layer.z) < loose[:, None]):
+                p0, p1 = layer.rowptr[j], layer.rowptr[j + 1]
+                mag = abs(float(layer.bias[j])) + float(np.abs(layer.val[p0:p1]).astype(np.float64) @ x_in[layer.colidx[p0:p1], b])
+                if abs(float(layer.z[j, b])) < (n_j[j] + 2.0) * 2.0 ** -24 * mag:
+                    state["seen"].append((li, int(j), int(b)))
+        for fl, j, b in state["flips"]:
+            if fl == li:
+                z = layer.z[j, b]
+                layer.z[j, b] = -z if z != 0 else np.float32(1e-30)
+                a[j, b] = oracle.all_relu(layer.z[j:j + 1, b], layer.act_kind, layer.act_parity, layer.alpha)[0]
+        return a
+
+    onet.after_forward = hook
+
+    def snapshot():
+        return [(O.val.copy(), O.vel.copy(), O.bias.copy(), O.bias_vel.copy()) for O in olayers]
+
+    def restore(snap):
+        for O, (val, vel, bias, bias_vel) in zip(olayers, snap):
+            O.set_state(O.rowptr, O.colidx, val, vel, bias, bias_vel)
+
+    def oracle_step(xs, ys, flips, collect=False):
+        state["flips"], state["seen"], state["collect"] = tuple(flips), [], collect
+        return onet.train_step(xs, ys)
+
+    def took_other_branch(li, j, b, gpu_grad):
+        O = olayers[li]
+        s_neg = -float(O.alpha) if O.act_parity == 0 else float(O.alpha)
+        s_cur, s_oth = (1.0, s_neg) if O.z[j, b] > 0 else (s_neg, 1.0)
+        if s_cur == 0.0:
+            return None                       # plain ReLU below zero: dz holds no trace of the incoming gradient
+        dz = float(O.dz[j, b])
+        p0, p1 = O.rowptr[j], O.rowptr[j + 1]
+        u = (dz / s_cur * s_oth - dz) * onet.acts[li][O.colidx[p0:p1], b].astype(np.float64)
+        if not u.any():
+            return 0.0
+        return float((gpu_grad[p0:p1].astype(np.float64) - O.grad_val[p0:p1]) @ u) / float(u @ u)
+
+    trace = bool(os.environ.get("SL_TEST_TRACE"))
+    loss_sum, on_kink, flipped = 0.0, 0, 0
+    for k in range(n_steps):
+        B = min(w.batch, X.shape[0] - k * w.batch)
+        xs, ys = blocks[k][:, :B], y[k * w.batch:k * w.batch + B]
+        before = snapshot()
+        loss = oracle_step(xs, ys, (), collect=True)
+        seen = list(state["seen"])
+        on_kink += len(seen)
+        gpu_grads = {}
+
+        def read_gradients(model):
+            for li in {key[0] for key in seen}:
+                gpu_grads[li] = model.layers[li].export_grad()[0]
+
+        net.train_step(xd[k], yd[k * w.batch:k * w.batch + B], B, before_update=read_gradients if seen else None)
+        # Deepest layer first: a branch taken differently there changes the gradient that flows back into the
+        # layers before it, so their rows are judged against the oracle re-run with the branches found so far.
+        other = []
+        for li in sorted({key[0] for key in seen}, reverse=True):
+            found = []
+            for fl, j, b in seen:
+                if fl != li:
+                    continue
+                t = took_other_branch(li, j, b, gpu_grads[li])
+                assert t is not None, "plain ReLU networks need the enumeration of run_network"
+                if t > 0.5:
+                    found.append((li, j, b))
+                if trace and t > 0.1:
+                    print(f"  step {k}: {(li, j, b)} t = {t:.3f}", flush=True)
+            if found:
+                other += found
+                restore(before)
+                loss = oracle_step(xs, ys, other)
+        flipped += len(other)
+        loss_sum += B * loss
+    print(f"{w.name}: {n_steps} steps, {on_kink} pre-activations on the kink, {flipped} took the other branch", flush=True)
+    assert abs(net.loss_sum.item() - loss_sum) <= tol_end * abs(loss_sum), "loss"
+    for li, (G, O) in enumerate(zip(net.layers, olayers)):
+        rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+        assert np.array_equal(rowptr, O.rowptr) and np.array_equal(colidx, O.colidx)
+        close(val, O.val, tol_end, f"val {li}")
+        close(vel, O.vel, tol_end, f"vel {li}")
+        close(bias, O.bias, tol_end, f"bias {li}")
+        close(bias_vel, O.bias_vel, tol_end, f"bias_vel {li}")
+    return net, onet, olayers
+
+
+@pytest.mark.parametrize("name", ["set_mlp_fmnist", "set_mlp_cifar"])
+def test_image_shaped_networks_whole_epoch(gpu, oracle, name):
+    """The FashionMNIST-shaped network for its epoch of 469 minibatches and the CIFAR-shaped one for its 391 (the
+    last minibatch of each is ragged), then one evolution from the oracle's trained weights."""
+    w = wl.WORKLOADS[name]
+    net, onet, olayers = run_network_stepwise(gpu, oracle, w, w.steps_per_epoch)
+    for G, O in zip(net.layers, olayers):
+        G.import_csr(O.rowptr, O.colidx, O.val, O.vel, O.bias, O.bias_vel)
+    net.evolve(w.zeta, 1)
+    onet.evolve(w.zeta, 1)
+    for G, O in zip(net.layers, olayers):
+        assert_same_topology(G, O)
+    net.close()
 
 
 def test_madelon_shaped_epoch_and_evolution(gpu, oracle):
