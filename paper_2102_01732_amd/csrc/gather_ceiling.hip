@@ -58,7 +58,7 @@ static void run(const std::vector<long> &row_counts, long total_bytes)
         CHECK(hipEventCreate(&a));
         CHECK(hipEventCreate(&b));
         const unsigned blocks = (unsigned)((ngroups + 256 / G - 1) / (256 / G));
-        for (int rep = 0; rep < 2; ++rep) {   // the second round is the measurement
+        for (int rep = 0; rep < 2; ++rep) {   // the second pass is the measurement
             CHECK(hipEventRecord(a));
             for (int i = 0; i < 5; ++i) hipLaunchKernelGGL(gather<G>, dim3(blocks), dim3(256), 0, 0, x, didx, ngroups, per, out);
             CHECK(hipEventRecord(b));
