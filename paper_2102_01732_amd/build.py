@@ -1,4 +1,5 @@
-"""Builds libsparse_set.so (gfx950) from csrc/*.hip with hipcc, in-tree."""
+"""Builds libsparse_set.so (gfx950) from csrc/*.hip with hipcc, in-tree, and the stand-alone
+gather-ceiling microbenchmark beside it."""
 from __future__ import annotations
 
 import os
@@ -11,6 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparse_set.so")
 SOURCES = ["sl_api.hip", "sl_train.hip", "sl_topology.hip"]
+TOOL_SRC, TOOL = "gather_ceiling.hip", os.path.join(HERE, "gather_ceiling")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wno-unused-result"]
 
@@ -27,9 +29,18 @@ def _compile(src: str) -> str:
     return obj
 
 
+def _tool() -> None:
+    cmd = ["hipcc", *FLAGS, os.path.join(CSRC, TOOL_SRC), "-o", TOOL]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for {TOOL_SRC}:\n" + "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l))
+
+
 def build(verbose: bool = False) -> str:
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
+    with ThreadPoolExecutor(max_workers=len(SOURCES) + 1) as ex:
+        tool = ex.submit(_tool)
         objs = list(ex.map(_compile, SOURCES))
+        tool.result()
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
