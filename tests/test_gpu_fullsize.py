@@ -2,7 +2,8 @@
 bench.py times (B = 128, all four layers on one GPU), against digests and sampled values that
 tests/golden/make_1m_golden.py computed with the CPU oracle alone.  Topology, indices and fresh
 weights are compared bit for bit over ALL entries (sha256); fp32 tensors on sampled neurons and
-every 8192nd connection, within 1e-4 of the tensor's largest oracle magnitude."""
+every 8192nd connection, within 1e-4 of the tensor's largest oracle magnitude after the first step and
+within 1e-3 after four steps."""
 import hashlib
 import json
 import os
@@ -92,4 +93,32 @@ def test_one_million_neuron_training_step(setup):
         near(val[idx], s["val"], np.abs(s["val"]).max(), 1e-4, f"layer {li} weights")
         near(vel[idx], s["vel"], s["vel_absmax"], 1e-4, f"layer {li} velocities")
         near(bias[np.asarray(s["rows"])], s["bias"], s["bias_absmax"], 1e-4, f"layer {li} biases")
+    net.close()
+
+
+def test_one_million_neuron_four_training_steps(setup):
+    """Four steps of the training loop that bench.py times (fused loss, chained backward, one update launch for
+    all layers) on minibatches 0..3, against the oracle's state after the same four steps."""
+    import torch
+    binding, golden, w = setup
+    after = golden["after_steps"]
+    steps, B = after["steps"], w.batch
+    X, y = wl.dataset(w, steps * B)
+    blocks = torch.from_numpy(wl.to_batch_blocks(X, B)).cuda()
+    yd = torch.from_numpy(y).cuda()
+    net = make_net(binding, w)
+    losses = []
+    for k in range(steps):
+        net.loss_sum.zero_()
+        net.train_step(blocks[k], yd[k * B:(k + 1) * B], B)
+        losses.append(net.loss_sum.item() / B)
+    for k, (got, ref) in enumerate(zip(losses, after["loss_means"])):
+        assert abs(got - ref) <= 1e-3 * abs(ref), f"loss of step {k + 1}: {got} vs {ref}"
+    stride = golden["val_stride"]
+    for li, (G, g, s1) in enumerate(zip(net.layers, after["layers"], golden["layers"])):
+        idx = np.arange(0, G.nnz, stride)
+        _, _, val, vel, bias, _ = G.export_csr()
+        near(val[idx], g["val"], g["val_absmax"], 1e-3, f"layer {li} weights after {steps} steps")
+        near(vel[idx], g["vel"], g["vel_absmax"], 1e-3, f"layer {li} velocities after {steps} steps")
+        near(bias[np.asarray(s1["step"]["rows"])], g["bias"], g["bias_absmax"], 1e-3, f"layer {li} biases after {steps} steps")
     net.close()
