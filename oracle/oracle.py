@@ -34,10 +34,11 @@ _u8p = np.ctypeslib.ndpointer(dtype=np.uint8, flags="C_CONTIGUOUS")
 
 
 def build(force: bool = False) -> str:
-    """Compile set_oracle.c with gcc (no fast-math, no FMA contraction)."""
+    """Compile set_oracle.c with gcc (no fast-math, no FMA contraction; OpenMP only shares loops whose
+    iterations own disjoint outputs, so results do not depend on the thread count)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
-            ["gcc", "-O2", "-ffp-contract=off", "-fPIC", "-shared", "-std=c11", _SRC, "-o", _LIB, "-lm"]
+            ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-std=c11", _SRC, "-o", _LIB, "-lm"]
         )
     return _LIB
 
@@ -48,6 +49,8 @@ def lib():
         build()
         L = ctypes.CDLL(_LIB)
         c = ctypes
+        L.or_set_threads.argtypes = [c.c_int]
+        L.or_set_threads.restype = c.c_int
         L.or_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
         L.or_philox4x32_10.restype = None
         L.or_weight_value.argtypes = [c.c_uint64, c.c_uint32, c.c_uint32, c.c_uint64, c.c_float]
@@ -91,6 +94,12 @@ def lib():
 # ----------------------------------------------------------------------------------------------
 # small helpers
 # ----------------------------------------------------------------------------------------------
+def set_threads(n: int = 0) -> int:
+    """Threads for the row-parallel loops of forward / backward / update (0: OpenMP's default, i.e.
+    OMP_NUM_THREADS or all cores).  Returns the number in use.  Results never depend on it."""
+    return int(lib().or_set_threads(int(n)))
+
+
 def philox(ctr: Sequence[int], key: Sequence[int]) -> np.ndarray:
     out = np.zeros(4, dtype=np.uint32)
     lib().or_philox4x32_10(np.asarray(ctr, dtype=np.uint32), np.asarray(key, dtype=np.uint32), out)

@@ -1,7 +1,7 @@
 /*
  * set_oracle.c -- TEST INFRASTRUCTURE ONLY.
  *
- * Plain, slow, single-threaded CPU oracle for the per-minibatch compute of a truly sparse MLP
+ * Plain, slow CPU oracle for the per-minibatch compute of a truly sparse MLP
  * layer trained with Sparse Evolutionary Training (SET), written from the paper
  * "Truly Sparse Neural Networks at Scale" (arXiv 2102.01732).  It exists so that the GPU
  * library can be checked against something that can be read next to the paper by eye.  It is
@@ -38,12 +38,34 @@
  *   or_importance(_f32)   neuron importance, eq. (4); Importance Pruning of Algorithm 2 removes the
  *                         incoming connections of neurons whose importance is below a threshold.
  *
- * Build: gcc -O2 -ffp-contract=off -fPIC -shared set_oracle.c -o liboracle.so -lm
+ * Threads: when built with -fopenmp, the loops of or_forward, or_backward and or_update whose
+ * iterations own disjoint outputs are shared among threads (rows j, or blocks of batch columns b for
+ * the input gradient).  Every output element is still produced by ONE thread, by the same
+ * additions in the same order as in the serial loop, so results do not depend on the thread count;
+ * or_set_threads(1) gives the single-threaded run.  Nothing else is threaded.
+ *
+ * Build: gcc -O2 -ffp-contract=off -fopenmp -fPIC -shared set_oracle.c -o liboracle.so -lm
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Number of threads for the loops described in the header (0 or less: the OpenMP default).  Returns
+ * the number that will be used (1 without OpenMP). */
+int or_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+    return omp_get_max_threads();
+#else
+    (void)n;
+    return 1;
+#endif
+}
 
 /* ------------------------------------------------------------------------------------------ */
 /* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3").  */
@@ -230,6 +252,7 @@ void or_forward(int64_t n_out, const int32_t *rowptr, const int32_t *colidx, con
                 const float *bias, const float *x, int64_t ldx, int32_t B, int act_kind,
                 int parity, float alpha, float *z, float *a, int64_t ldo)
 {
+#pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < n_out; ++j) {
         for (int32_t b = 0; b < B; ++b) {
             double acc = (double)bias[j];
@@ -255,6 +278,7 @@ int or_backward(int64_t n_in, int64_t n_out, const int32_t *rowptr, const int32_
                 float alpha, float *dz, float *grad_val, float *grad_bias, float *grad_x,
                 int64_t ldgx)
 {
+#pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < n_out; ++j) {
         double sb = 0.0;
         for (int32_t b = 0; b < B; ++b) {
@@ -273,12 +297,19 @@ int or_backward(int64_t n_in, int64_t n_out, const int32_t *rowptr, const int32_
     if (grad_x) {
         double *acc = (double *)calloc((size_t)n_in * (size_t)B, sizeof(double));
         if (!acc) return -2;
-        for (int64_t j = 0; j < n_out; ++j)
-            for (int32_t p = rowptr[j]; p < rowptr[j + 1]; ++p) {
-                int64_t i = colidx[p];
-                for (int32_t b = 0; b < B; ++b)
-                    acc[i * B + b] += (double)val[p] * (double)dz[j * ldo + b];
-            }
+        /* blocks of eight batch columns are independent of each other: each (i, b) still receives its
+         * terms in ascending (j, p) order */
+#pragma omp parallel for schedule(static)
+        for (int32_t b0 = 0; b0 < B; b0 += 8) {
+            int32_t b1 = b0 + 8 < B ? b0 + 8 : B;
+            for (int64_t j = 0; j < n_out; ++j)
+                for (int32_t p = rowptr[j]; p < rowptr[j + 1]; ++p) {
+                    int64_t i = colidx[p];
+                    for (int32_t b = b0; b < b1; ++b)
+                        acc[i * B + b] += (double)val[p] * (double)dz[j * ldo + b];
+                }
+        }
+#pragma omp parallel for schedule(static)
         for (int64_t i = 0; i < n_in; ++i)
             for (int32_t b = 0; b < B; ++b) grad_x[i * ldgx + b] = (float)acc[i * B + b];
         free(acc);
@@ -316,6 +347,7 @@ void or_dropout_apply(float *a, const uint8_t *keep, int64_t n, float scale)
 void or_update(int64_t n, float *val, float *vel, const float *grad, float lr, float momentum,
                float weight_decay)
 {
+#pragma omp parallel for schedule(static)
     for (int64_t t = 0; t < n; ++t) {
         float g = grad[t] + weight_decay * val[t];
         float v = momentum * vel[t] - lr * g;

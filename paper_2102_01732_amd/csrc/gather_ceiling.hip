@@ -3,7 +3,7 @@
 // B = 32, 128, 256) as a function of the number of rows of the operand they come from.  It gives the
 // ceiling the sparse kernels are measured against.  At 512-byte rows: ~26 TB/s while the operand fits the
 // 4 MB L2 of an XCD, ~8.5 TB/s at 32 MB, ~7.5 TB/s at 512 MB (L2 miss path), ~6.8 TB/s at 2 GB.
-//   python -m paper_2102_01732_amd.build && paper_2102_01732_amd/gather_ceiling
+//   python -m paper_2102_01732_amd.build --gather-ceiling && paper_2102_01732_amd/gather_ceiling
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdlib>

@@ -1,0 +1,134 @@
+"""Helpers shared by the GPU parity tests.  Everything here runs on the CPU and calls only the oracle.
+
+Comparison rule.  An fp32 sum of n products carries a rounding error of at most about n 2^-24 times the sum of
+the MAGNITUDES of its terms, whatever the value of the sum itself is; so besides the two tensor-wide checks
+(largest error against the largest oracle magnitude, and the 2-norm of the error against the 2-norm of the
+oracle's tensor) every element is held to  |gpu - oracle| <= tol * (sum of |terms| of that element), which is
+what "relative 1e-4" can mean for an element that is small because its terms cancel.  The magnitude sums come
+from the oracle's own routines run on absolute values.
+
+The kink of eq. (3).  f' jumps at z = 0.  The oracle adds a row in double, the kernel in fp32 in another order,
+so a pre-activation whose exact value lies within the kernel's worst-case rounding error of zero,
+|z_jb| < (n_j + 2) 2^-24 (|b_j| + sum_i |w_ji| |x_ib|) (plus what the same error in the layers before
+contributes through x), may take either branch and both results are correct evaluations of the method.  Such a neuron is "in the band" (decided from oracle values alone).  Its own
+gradients, and those of every neuron its delta flows back into during the same step, are left out of the
+comparisons of that step (a neuron is in the band in very few steps, so every neuron is compared in almost
+all of them)."""
+import numpy as np
+
+U24 = 2.0 ** -24
+
+
+def close(got, ref, tol, what="", mag=None, rows=None):
+    """Tensor-wide checks (max-abs against the largest oracle magnitude, and normwise); with `mag` also the
+    element-wise check |got - ref| <= tol * mag.  `rows` (bool mask over axis 0) restricts all of them."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, what
+    if rows is not None:
+        got, ref = got[rows], ref[rows]
+        if mag is not None:
+            mag = np.asarray(mag)[rows]
+    assert np.all(np.isfinite(got)), what
+    if ref.size == 0:
+        return 0.0
+    scale = np.abs(ref).max()
+    if scale == 0:
+        assert np.abs(got).max() == 0, what
+        return 0.0
+    diff = np.abs(got - ref)
+    err = diff.max()
+    assert err <= tol * scale, f"{what}: max abs err {err:.3e} > {tol} * {scale:.3e}"
+    nrm = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    assert nrm <= tol, f"{what}: normwise err {nrm:.3e} > {tol}"
+    worst = err / scale / tol
+    if mag is not None:
+        mag = np.asarray(mag, dtype=np.float64)
+        assert mag.shape == ref.shape, what
+        bound = tol * np.maximum(mag, np.finfo(np.float32).tiny)
+        bad = diff > bound
+        if bad.any():
+            at = np.unravel_index(np.argmax(diff / bound), diff.shape)
+            raise AssertionError(f"{what}: {int(bad.sum())} elements beyond {tol} * sum|terms|; worst at {at}: "
+                                 f"got {got[at]!r} ref {ref[at]!r} sum|terms| {mag[at]!r}")
+        worst = max(worst, float((diff / bound).max()))
+    return worst
+
+
+def abs_forward(orc, O, x, with_bias=True):
+    """[n_out, B] float32: |b_j| + sum_i |w_ji| x_ib for a non-negative x (the oracle's forward routine run on
+    absolute values); without the bias term if with_bias is False."""
+    x = np.ascontiguousarray(np.abs(x), dtype=np.float32)
+    B = x.shape[1]
+    m = np.zeros((O.n_out, B), dtype=np.float32)
+    a = np.zeros((O.n_out, B), dtype=np.float32)
+    bias = np.abs(O.bias) if with_bias else np.zeros(O.n_out, np.float32)
+    val = np.abs(O.val) if O.nnz else np.zeros(1, np.float32)
+    orc.lib().or_forward(O.n_out, O.rowptr, O.colidx, val, bias, x, B, B, 0, 0, np.float32(0), m, a, B)
+    return m
+
+
+def abs_backward(orc, O, x, dz, need_input_grad=True):
+    """Magnitude sums of the backward pass: (sum_b |dz_jb||x_ib| per stored connection, sum_b |dz_jb| per neuron,
+    sum_j |w_ji||dz_jb| per input element or None), by the oracle's backward routine on absolute values."""
+    x = np.ascontiguousarray(np.abs(x), dtype=np.float32)
+    d = np.ascontiguousarray(np.abs(dz), dtype=np.float32)
+    B = x.shape[1]
+    scratch = np.zeros_like(d)
+    g = np.zeros(max(O.nnz, 1), dtype=np.float32)
+    gb = np.zeros(O.n_out, dtype=np.float32)
+    gx = np.zeros((O.n_in, B), dtype=np.float32) if need_input_grad else None
+    rc = orc.lib().or_backward(O.n_in, O.n_out, O.rowptr, O.colidx, np.abs(O.val) if O.nnz else np.zeros(1, np.float32),
+                               x, B, d, d, B, B, 0, 0, np.float32(0), scratch, g, gb,
+                               gx.ctypes.data if gx is not None else None, B)
+    assert rc == 0
+    return g[: O.nnz], gb, gx
+
+
+def forward_bounds(orc, O, mag_in, err_in):
+    """For layer O fed with an input whose elements are bounded by mag_in and which the kernel knows to within
+    err_in: (mag_z, err_z) = (|b_j| + sum_i |w_ji| mag_in, (n_j + 2) 2^-24 mag_z + sum_i |w_ji| err_in): the sum of
+    magnitudes behind every pre-activation, and the most by which an fp32 evaluation in any order, of inputs
+    that are themselves off by err_in, can differ from the exact value.  Since |f(z)| <= |z| and f is
+    1-Lipschitz (alpha <= 1), both also bound the activation."""
+    mag_z = abs_forward(orc, O, mag_in)
+    n_j = np.diff(O.rowptr).astype(np.float32)
+    err_z = ((n_j + 2.0) * np.float32(U24))[:, None] * mag_z
+    if err_in is not None:
+        err_z = err_z + abs_forward(orc, O, err_in, with_bias=False)
+    return mag_z, err_z
+
+
+def band(O, err_z):
+    """bool [n_out, B]: pre-activations of layer O (after O.forward) that lie within err_z of the kink.  All False
+    for an identity (output) layer."""
+    if not O.act_kind:
+        return np.zeros(O.z.shape, dtype=bool)
+    return np.abs(O.z) < err_z
+
+
+def slope_magnitude(O):
+    """|f'(z)| of layer O's last forward: 1 above the kink, alpha at or below it (1 for an identity layer)."""
+    if not O.act_kind:
+        return np.ones(O.z.shape, np.float32)
+    return np.where(O.z > 0, np.float32(1.0), np.float32(abs(float(O.alpha)))).astype(np.float32)
+
+
+def entry_rows(O):
+    return np.repeat(np.arange(O.n_out), np.diff(O.rowptr))
+
+
+def reach_sets(olayers, band_rows):
+    """band_rows[li]: bool [n_out] neurons of layer li with a pre-activation in the band.  Returns, per layer, the
+    neurons whose delta of this step may differ between two correct evaluations: the band neurons themselves and
+    every neuron that feeds a neuron of the next layer's set (deltas flow back along stored connections)."""
+    reach = [None] * len(olayers)
+    nxt = None
+    for li in range(len(olayers) - 1, -1, -1):
+        r = band_rows[li].copy()
+        if nxt is not None and nxt.any():
+            up = olayers[li + 1]
+            r[up.colidx[nxt[entry_rows(up)]]] = True
+        reach[li] = r
+        nxt = r
+    return reach

@@ -1,0 +1,92 @@
+"""Minibatch-by-minibatch parity in which NO value of the GPU ever reaches the oracle.
+
+The oracle trains freely.  Before every minibatch its state (pattern, weights, velocities, biases) is imported
+into the GPU network, both sides take the same training step, and activations, gradients, and the updated
+weights, velocities and biases are compared at the one-step tolerance.  Neurons whose pre-activation lies in the
+rounding band of eq. (3)'s kink (see parity_util), and the neurons their deltas flow back into, are left out of
+the element-wise comparisons of that step; the band is computed from oracle values only."""
+import numpy as np
+
+from paper_2102_01732_amd import workloads as wl
+from parity_util import abs_backward, band, close, entry_rows, forward_bounds, reach_sets, slope_magnitude
+
+
+def make_oracle_net(orc, w):
+    olayers = [orc.OracleLayer(s.n_in, s.n_out, s.nnz, s.act_kind, s.act_parity, w.alpha, s.init_limit, w.lr,
+                               w.momentum, 0.0, w.seed, s.layer_id) for s in w.layers]
+    return orc.OracleMLP(olayers), olayers
+
+
+def run_stepwise_oracle_only(gpu, orc, w, n_steps, tol=1e-4, net=None, oracle_net=None, log=print):
+    import torch
+    X, y = wl.dataset(w, n_steps * w.batch)
+    blocks = wl.to_batch_blocks(X, w.batch)
+    if net is None:
+        net = gpu.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=w.batch)
+    onet, olayers = oracle_net if oracle_net is not None else make_oracle_net(orc, w)
+    yd = torch.from_numpy(y).cuda()
+    n_layers = len(olayers)
+    bands, mags = [None] * n_layers, [None] * n_layers
+    chain = {}
+
+    def hook(li, layer, a):
+        if li == 0:
+            chain["mag"], chain["err"] = np.abs(onet.acts[0]), None     # the inputs are the same bits on both sides
+        mags[li], chain["err"] = forward_bounds(orc, layer, chain["mag"], chain["err"])
+        chain["mag"] = mags[li]
+        bands[li] = band(layer, chain["err"])
+        return a
+
+    onet.after_forward = hook
+    stats = dict(steps=0, band=0, worst=0.0, left_out=[0] * n_layers)
+    for k in range(n_steps):
+        B = min(w.batch, X.shape[0] - k * w.batch)
+        xs, ys = blocks[k][:, :B], y[k * w.batch:k * w.batch + B]
+        for G, O in zip(net.layers, olayers):
+            G.import_csr(O.rowptr, O.colidx, O.val, O.vel, O.bias, O.bias_vel)
+        before = [(O.val.copy(), O.vel.copy(), O.bias.copy(), O.bias_vel.copy()) for O in olayers]
+        loss_ref = onet.train_step(xs, ys)
+        got = {}
+
+        def read(model):
+            got["grads"] = [L.export_grad() for L in model.layers]
+            got["acts"] = [a[:, :B].cpu().numpy() for a in model.acts]
+
+        net.loss_sum.zero_()
+        net.train_step(torch.from_numpy(np.ascontiguousarray(blocks[k])).cuda(), yd[k * w.batch:k * w.batch + B], B,
+                       before_update=read)
+        loss = net.loss_sum.item() / B
+        assert abs(loss - loss_ref) <= tol * max(abs(loss_ref), 1e-30), f"step {k}: loss {loss} vs {loss_ref}"
+        reach = reach_sets(olayers, [b.any(axis=1) for b in bands])
+        stats["band"] += int(sum(b.sum() for b in bands))
+        worst = 0.0
+        mag_dz = np.abs(olayers[-1].dz)
+        for li in range(n_layers - 1, -1, -1):
+            G, O = net.layers[li], olayers[li]
+            tag = f"step {k} layer {li}"
+            # a = f(z) is continuous at the kink: every activation is compared
+            worst = max(worst, close(got["acts"][li], onet.acts[li + 1], tol, tag + " activations", mag=mags[li]))
+            ok = ~reach[li]
+            stats["left_out"][li] += int(reach[li].sum())
+            e_ok = ok[entry_rows(O)]
+            x_mag = np.abs(onet.acts[0]) if li == 0 else mags[li - 1]
+            mg, mgb, mgx = abs_backward(orc, O, x_mag, mag_dz, need_input_grad=li > 0)
+            g, gb = got["grads"][li]
+            worst = max(worst, close(g, O.grad_val, tol, tag + " weight gradient", mag=mg, rows=e_ok))
+            worst = max(worst, close(gb, O.grad_bias, tol, tag + " bias gradient", mag=mgb, rows=ok))
+            _, _, val, vel, bias, bias_vel = G.export_csr()
+            lr = float(O.lr)
+            val0, vel0, bias0, bvel0 = before[li]
+            worst = max(worst, close(vel, O.vel, tol, tag + " velocities", mag=np.abs(vel0) + lr * mg, rows=e_ok))
+            worst = max(worst, close(val, O.val, tol, tag + " weights", mag=np.abs(val0) + np.abs(vel0) + lr * mg, rows=e_ok))
+            worst = max(worst, close(bias_vel, O.bias_vel, tol, tag + " bias velocities", mag=np.abs(bvel0) + lr * mgb, rows=ok))
+            worst = max(worst, close(bias, O.bias, tol, tag + " biases", mag=np.abs(bias0) + np.abs(bvel0) + lr * mgb, rows=ok))
+            if li > 0:
+                mag_dz = mgx * slope_magnitude(olayers[li - 1])
+        stats["steps"] += 1
+        stats["worst"] = max(stats["worst"], worst)
+        if log and (k % 50 == 0 or k == n_steps - 1):
+            log(f"{w.name}: step {k}: loss {loss_ref:.6g}, {stats['band']} pre-activations in the band so far, "
+                f"largest error / allowed = {stats['worst']:.3f}", flush=True)
+    onet.after_forward = None
+    return net, onet, olayers, stats

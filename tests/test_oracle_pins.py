@@ -567,3 +567,48 @@ def test_random_tiny_layers_against_dense_matrices_and_set_invariants(oracle):
     seen = {"layers": 0, "evolved": 0}
     run()
     assert seen["layers"] >= 50 and seen["evolved"] >= 30
+
+
+def test_results_do_not_depend_on_the_thread_count(oracle):
+    """The oracle may share rows (and, for the input gradient, blocks of batch columns) among threads; every output
+    is still added up by one thread in the serial order, so one thread and many give the same bits."""
+    rng = np.random.default_rng(17)
+    n_in, n_out, nnz, B = 300, 257, 9000, 37
+    x = rng.standard_normal((n_in, B)).astype(np.float32)
+    ga = rng.standard_normal((n_out, B)).astype(np.float32)
+    outs = []
+    many = oracle.set_threads(0)
+    for threads in (1, max(2, many), 3):
+        assert oracle.set_threads(threads) == threads
+        O = oracle.OracleLayer(n_in, n_out, nnz, 1, 0, 0.6, 0.3, 0.01, 0.9, 0.01, 5, 1)
+        a = O.forward(x)
+        gx = O.backward(x, ga)
+        O.update()
+        outs.append([a, gx, O.grad_val.copy(), O.grad_bias.copy(), O.val.copy(), O.vel.copy(), O.bias.copy()])
+    oracle.set_threads(many)
+    for other in outs[1:]:
+        for u, v in zip(outs[0], other):
+            assert np.array_equal(u.view(np.uint32), v.view(np.uint32))
+
+
+def test_rounding_band_covers_an_fp32_evaluation(oracle):
+    """The error bound the GPU tests use around the kink of eq. (3), (n_j + 2) 2^-24 (|b_j| + sum |w||x|), propagated
+    through the layers, must cover what a float32 evaluation in another order really does: here scipy's float32
+    CSR product (a library routine) through three layers, against the oracle's double accumulation."""
+    from parity_util import forward_bounds
+    rng = np.random.default_rng(23)
+    dims = (300, 400, 350, 200)
+    x = rng.standard_normal((dims[0], 64)).astype(np.float32)
+    a_ref, a32 = x, x
+    mag, err = np.abs(x), None
+    for li in range(3):
+        O = make_layer(oracle, dims[li], dims[li + 1], 20 * (dims[li] + dims[li + 1]), 1, li % 2, 0.6, seed=77, layer_id=li)
+        O.bias = (rng.standard_normal(dims[li + 1]) * 0.1).astype(np.float32)
+        a_ref = O.forward(a_ref)
+        W32 = sp.csr_matrix((O.val, O.colidx, O.rowptr), shape=(O.n_out, O.n_in))
+        z32 = (W32 @ a32 + O.bias[:, None]).astype(np.float32)
+        a32 = np.where(z32 > 0, z32, (np.float32(-0.6) if li % 2 == 0 else np.float32(0.6)) * z32).astype(np.float32)
+        mag, err = forward_bounds(oracle, O, mag, err)
+        assert np.all(np.abs(a_ref) <= mag)
+        assert np.all(np.abs(a32.astype(np.float64) - a_ref) <= err)
+        assert np.all(err <= 1e-4 * mag) and err.max() > 0
