@@ -10,36 +10,48 @@ from the oracle's own routines run on absolute values.
 The kink of eq. (3).  f' jumps at z = 0.  The oracle adds a row in double, the kernel in fp32 in another order,
 so a pre-activation whose exact value lies within the kernel's worst-case rounding error of zero,
 |z_jb| < (n_j + 2) 2^-24 (|b_j| + sum_i |w_ji| |x_ib|) (plus what the same error in the layers before
-contributes through x), may take either branch and both results are correct evaluations of the method.  Such a neuron is "in the band" (decided from oracle values alone).  Its own
-gradients, and those of every neuron its delta flows back into during the same step, are left out of the
-comparisons of that step (a neuron is in the band in very few steps, so every neuron is compared in almost
-all of them)."""
+contributes through x), may take either branch and both results are correct evaluations of the method.  Such a
+pre-activation is "in the band" (decided from oracle values alone).  The other branch changes that neuron's
+delta for that sample by at most (1 + alpha) |dLoss/da|, and the change flows back along the stored connections
+like any delta.  kink_allowance() bounds, per element, how far a correct result may therefore lie from the
+oracle's; close() takes that allowance off the element's error before any check.
+"""
 import numpy as np
 
 U24 = 2.0 ** -24
 
 
-def close(got, ref, tol, what="", mag=None, rows=None):
-    """Tensor-wide checks (max-abs against the largest oracle magnitude, and normwise); with `mag` also the
-    element-wise check |got - ref| <= tol * mag.  `rows` (bool mask over axis 0) restricts all of them."""
+def close(got, ref, tol, what="", mag=None, rows=None, allow=None, tally=None):
+    """Tensor-wide checks (largest error against tol * the largest oracle magnitude, and 2-norm of the error
+    against tol * the 2-norm of the oracle's tensor); with `mag` also the element-wise check
+    |got - ref| <= tol * mag.  `allow` (per element, >= 0: see kink_delta) is subtracted from every element's
+    error first.  `rows` (bool mask over axis 0) restricts everything.  Returns the largest error as a fraction of
+    what was allowed.  `tally` (dict) counts the elements checked and those that needed their allowance, i.e. lay
+    beyond tol * mag before it was taken off."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, what
     if rows is not None:
         got, ref = got[rows], ref[rows]
-        if mag is not None:
-            mag = np.asarray(mag)[rows]
+        mag = None if mag is None else np.asarray(mag)[rows]
+        allow = None if allow is None else np.asarray(allow)[rows]
     assert np.all(np.isfinite(got)), what
     if ref.size == 0:
         return 0.0
+    diff = np.abs(got - ref)
+    if tally is not None:
+        tally["checked"] = tally.get("checked", 0) + diff.size
+        if allow is not None and mag is not None:
+            tally["needed"] = tally.get("needed", 0) + int((diff > tol * np.asarray(mag, dtype=np.float64)).sum())
+    if allow is not None:
+        diff = np.maximum(diff - np.asarray(allow, dtype=np.float64), 0.0)
     scale = np.abs(ref).max()
     if scale == 0:
-        assert np.abs(got).max() == 0, what
+        assert diff.max() == 0, what
         return 0.0
-    diff = np.abs(got - ref)
     err = diff.max()
     assert err <= tol * scale, f"{what}: max abs err {err:.3e} > {tol} * {scale:.3e}"
-    nrm = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    nrm = np.linalg.norm(diff) / np.linalg.norm(ref)
     assert nrm <= tol, f"{what}: normwise err {nrm:.3e} > {tol}"
     worst = err / scale / tol
     if mag is not None:
@@ -118,17 +130,13 @@ def entry_rows(O):
     return np.repeat(np.arange(O.n_out), np.diff(O.rowptr))
 
 
-def reach_sets(olayers, band_rows):
-    """band_rows[li]: bool [n_out] neurons of layer li with a pre-activation in the band.  Returns, per layer, the
-    neurons whose delta of this step may differ between two correct evaluations: the band neurons themselves and
-    every neuron that feeds a neuron of the next layer's set (deltas flow back along stored connections)."""
-    reach = [None] * len(olayers)
-    nxt = None
-    for li in range(len(olayers) - 1, -1, -1):
-        r = band_rows[li].copy()
-        if nxt is not None and nxt.any():
-            up = olayers[li + 1]
-            r[up.colidx[nxt[entry_rows(up)]]] = True
-        reach[li] = r
-        nxt = r
-    return reach
+def kink_delta(O, in_band, mag_ga, allow_ga):
+    """Bound on how far dz of layer O may lie from the oracle's, per element: the incoming gradient dLoss/da is
+    itself uncertain by allow_ga (flips in the layers after this one) and bounded by mag_ga; an element in
+    the band may in addition have taken the other branch of eq. (3)."""
+    slope = slope_magnitude(O)
+    allow = slope * allow_ga
+    if O.act_kind and in_band.any():
+        a = np.float32(1.0 + abs(float(O.alpha)))
+        allow = np.where(in_band, a * (mag_ga + allow_ga) + allow_ga, allow).astype(np.float32)
+    return allow

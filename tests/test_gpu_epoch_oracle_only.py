@@ -25,9 +25,10 @@ def test_every_minibatch_of_an_epoch_from_the_oracles_state(gpu, oracle, name):
     w = wl.WORKLOADS[name]
     net, onet, olayers, stats = run_stepwise_oracle_only(gpu, oracle, w, w.steps_per_epoch)
     assert stats["steps"] == w.steps_per_epoch
-    # the band must stay a rare event, or the comparison would be hollow
-    total_rows = sum(s.n_out for s in w.layers[:-1]) * w.steps_per_epoch
-    assert sum(stats["left_out"]) <= 0.02 * total_rows, stats
+    # The band is a worst-case bound, so nearly all pre-activations in it still take the oracle's branch: all but a
+    # sliver of the gradient elements must meet the plain 1e-4 bound without any kink allowance.
+    for t in stats["tally"]:
+        assert t["needed"] <= 0.002 * t["checked"], stats
     # then the evolution of Algorithm 2, from the oracle's trained state on both sides
     for G, O in zip(net.layers, olayers):
         G.import_csr(O.rowptr, O.colidx, O.val, O.vel, O.bias, O.bias_vel)
