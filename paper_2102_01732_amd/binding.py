@@ -323,15 +323,18 @@ class SparseMLP:
             xin = x if li == 0 else self.acts[li - 1]
             self.layers[li].backward(xin, self.grad_out if li == last else None, B, None)
 
-    def train_step(self, x: torch.Tensor, y: torch.Tensor, B: int, before_update=None):
+    def train_step(self, x: torch.Tensor, y: torch.Tensor, B: int, before_update=None, after_forward=None):
         """x [n_in][ld>=B] feature-major, y int32 [B].  Forward, loss written into the output layer,
         chained backward, one update launch for all layers.  `before_update(self)`, if given, runs between
-        the backward pass and the update (the gradients can be read with SparseLayer.export_grad there)."""
+        the backward pass and the update (the gradients can be read with SparseLayer.export_grad there);
+        `after_forward(self)` runs between the forward pass and the loss (self.acts[-1] holds the logits there)."""
         if self.dropout > 0.0:
             for layer in self.layers[:-1]:
                 layer.set_dropout(self.dropout, self.step_index)
         self.step_index += 1
         zL = self.forward(x, B)
+        if after_forward is not None:
+            after_forward(self)
         last = self.layers[-1]
         last._check(lib().sparse_loss_softmax_ce_into(last.handle, zL.data_ptr(), zL.stride(0), y.data_ptr(), B,
                                                       self.loss_sum.data_ptr(), _stream()), "sparse_loss_softmax_ce_into")

@@ -1,7 +1,7 @@
 """Writes tests/golden/set_mlp_1m_step.json: digests and sampled values of ONE evolution, of the
-first training step and of the state after FOUR training steps of the one-million-neuron
-workload, computed by the CPU oracle alone (about ten minutes on one core).  Nothing from the
-GPU path is read or stored.
+first training step and of the states after FOUR and after SIXTEEN training steps of the
+one-million-neuron workload, computed by the CPU oracle alone (about half an hour on one core, a
+few minutes on eight).  Nothing from the GPU path is read or stored.
 
     python tests/golden/make_1m_golden.py
 """
@@ -21,6 +21,7 @@ from paper_2102_01732_amd import workloads as wl      # noqa: E402
 ROW_SAMPLES = 48       # sampled neurons per layer (full batch rows are stored)
 VAL_STRIDE = 8192      # every VAL_STRIDE-th stored connection
 STEPS = 4              # training steps (minibatches 0..3) behind the "after_steps" values
+MORE_STEPS = 16        # ... and behind the "after_more_steps" values
 
 
 def digest(a):
@@ -35,7 +36,7 @@ def sample_rows(n, layer_id):
 def main():
     w = wl.WORKLOADS["set_mlp_1m"]
     t0 = time.time()
-    X, y = wl.dataset(w, STEPS * w.batch)
+    X, y = wl.dataset(w, MORE_STEPS * w.batch)
     blocks = wl.to_batch_blocks(X, w.batch)
     x0, y_all, y = blocks[0], y, y[: w.batch]
     layers = [orc.OracleLayer(s.n_in, s.n_out, s.nnz, s.act_kind, s.act_parity, w.alpha, s.init_limit, w.lr,
@@ -73,20 +74,27 @@ def main():
             "bias": L.bias[rows].astype(np.float64).tolist(),
             "bias_absmax": float(np.abs(L.bias).max()),
         }
-    # three more steps on the next minibatches; the state after the fourth is sampled the same way
+    # more steps on the next minibatches; the states after the fourth and the sixteenth are sampled the same way
     losses = [loss]
-    for k in range(1, STEPS):
+
+    def sampled_state():
+        rec = []
+        for li, L in enumerate(layers):
+            rows = sample_rows(L.n_out, li)
+            idx = np.arange(0, L.nnz, VAL_STRIDE)
+            rec.append({
+                "val": L.val[idx].astype(np.float64).tolist(), "val_absmax": float(np.abs(L.val).max()),
+                "vel": L.vel[idx].astype(np.float64).tolist(), "vel_absmax": float(np.abs(L.vel).max()),
+                "bias": L.bias[rows].astype(np.float64).tolist(), "bias_absmax": float(np.abs(L.bias).max()),
+            })
+        return rec
+
+    for k in range(1, MORE_STEPS):
         losses.append(net.train_step(blocks[k], y_all[k * w.batch:(k + 1) * w.batch]))
         print("step", k + 1, time.time() - t0, flush=True)
-    out["after_steps"] = {"steps": STEPS, "loss_means": losses, "layers": []}
-    for li, L in enumerate(layers):
-        rows = sample_rows(L.n_out, li)
-        idx = np.arange(0, L.nnz, VAL_STRIDE)
-        out["after_steps"]["layers"].append({
-            "val": L.val[idx].astype(np.float64).tolist(), "val_absmax": float(np.abs(L.val).max()),
-            "vel": L.vel[idx].astype(np.float64).tolist(), "vel_absmax": float(np.abs(L.vel).max()),
-            "bias": L.bias[rows].astype(np.float64).tolist(), "bias_absmax": float(np.abs(L.bias).max()),
-        })
+        if k + 1 == STEPS:
+            out["after_steps"] = {"steps": STEPS, "loss_means": list(losses), "layers": sampled_state()}
+    out["after_more_steps"] = {"steps": MORE_STEPS, "loss_means": list(losses), "layers": sampled_state()}
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "set_mlp_1m_step.json")
     json.dump(out, open(path, "w"))
     print("wrote", path, os.path.getsize(path), "bytes in", time.time() - t0, "s")

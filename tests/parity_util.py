@@ -50,7 +50,11 @@ def close(got, ref, tol, what="", mag=None, rows=None, allow=None, tally=None):
         assert diff.max() == 0, what
         return 0.0
     err = diff.max()
-    assert err <= tol * scale, f"{what}: max abs err {err:.3e} > {tol} * {scale:.3e}"
+    if err > tol * scale:
+        at = np.unravel_index(np.argmax(diff), diff.shape)
+        raise AssertionError(f"{what}: max abs err {err:.3e} > {tol} * {scale:.3e} at {at}: got {got[at]!r} ref {ref[at]!r}"
+                             + (f" sum|terms| {np.asarray(mag)[at]!r}" if mag is not None else "")
+                             + (f" kink allowance {np.asarray(allow)[at]!r}" if allow is not None else ""))
     nrm = np.linalg.norm(diff) / np.linalg.norm(ref)
     assert nrm <= tol, f"{what}: normwise err {nrm:.3e} > {tol}"
     worst = err / scale / tol
@@ -80,9 +84,10 @@ def abs_forward(orc, O, x, with_bias=True):
     return m
 
 
-def abs_backward(orc, O, x, dz, need_input_grad=True):
+def abs_backward(orc, O, x, dz, need_input_grad=True, val=None):
     """Magnitude sums of the backward pass: (sum_b |dz_jb||x_ib| per stored connection, sum_b |dz_jb| per neuron,
-    sum_j |w_ji||dz_jb| per input element or None), by the oracle's backward routine on absolute values."""
+    sum_j |w_ji||dz_jb| per input element or None), by the oracle's backward routine on absolute values.  `val`:
+    the weights to use when O.val no longer holds the ones the backward pass saw (after an update)."""
     x = np.ascontiguousarray(np.abs(x), dtype=np.float32)
     d = np.ascontiguousarray(np.abs(dz), dtype=np.float32)
     B = x.shape[1]
@@ -90,7 +95,8 @@ def abs_backward(orc, O, x, dz, need_input_grad=True):
     g = np.zeros(max(O.nnz, 1), dtype=np.float32)
     gb = np.zeros(O.n_out, dtype=np.float32)
     gx = np.zeros((O.n_in, B), dtype=np.float32) if need_input_grad else None
-    rc = orc.lib().or_backward(O.n_in, O.n_out, O.rowptr, O.colidx, np.abs(O.val) if O.nnz else np.zeros(1, np.float32),
+    w = np.abs(O.val if val is None else val) if O.nnz else np.zeros(1, np.float32)
+    rc = orc.lib().or_backward(O.n_in, O.n_out, O.rowptr, O.colidx, np.ascontiguousarray(w, dtype=np.float32),
                                x, B, d, d, B, B, 0, 0, np.float32(0), scratch, g, gb,
                                gx.ctypes.data if gx is not None else None, B)
     assert rc == 0

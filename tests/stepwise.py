@@ -17,7 +17,15 @@ def make_oracle_net(orc, w):
     return orc.OracleMLP(olayers), olayers
 
 
-def run_stepwise_oracle_only(gpu, orc, w, n_steps, tol=1e-4, net=None, oracle_net=None, log=print):
+def run_stepwise_oracle_only(gpu, orc, w, n_steps, tol=1e-4, net=None, oracle_net=None, log=print, first_step=0,
+                             oracle_logits=False):
+    """Minibatches first_step .. n_steps-1 (pass the same `net` and `oracle_net` to continue an earlier call).
+
+    oracle_logits: after the GPU's forward pass (whose activations and logits are compared as always) the ORACLE's
+    logits replace the GPU's before the loss is taken.  Needed where the softmax is ill-conditioned: the
+    10^6-neuron network's logits are sums of a million terms and reach thousands, so a rounding difference that is
+    1e-6 of such a sum can move a probability by O(1) when two logits happen to be close, and with it that sample's
+    whole backward pass -- a property of the workload, not of either implementation."""
     import torch
     X, y = wl.dataset(w, n_steps * w.batch)
     blocks = wl.to_batch_blocks(X, w.batch)
@@ -39,7 +47,7 @@ def run_stepwise_oracle_only(gpu, orc, w, n_steps, tol=1e-4, net=None, oracle_ne
 
     onet.after_forward = hook
     stats = dict(steps=0, band=0, worst=0.0, tally=[dict(checked=0, needed=0) for _ in range(n_layers)])
-    for k in range(n_steps):
+    for k in range(first_step, n_steps):
         B = min(w.batch, X.shape[0] - k * w.batch)
         xs, ys = blocks[k][:, :B], y[k * w.batch:k * w.batch + B]
         for G, O in zip(net.layers, olayers):
@@ -50,11 +58,15 @@ def run_stepwise_oracle_only(gpu, orc, w, n_steps, tol=1e-4, net=None, oracle_ne
 
         def read(model):
             got["grads"] = [L.export_grad() for L in model.layers]
+
+        def after_forward(model):
             got["acts"] = [a[:, :B].cpu().numpy() for a in model.acts]
+            if oracle_logits:
+                model.acts[-1][:, :B] = torch.from_numpy(onet.acts[-1]).to(model.acts[-1].device)
 
         net.loss_sum.zero_()
         net.train_step(torch.from_numpy(np.ascontiguousarray(blocks[k])).cuda(), yd[k * w.batch:k * w.batch + B], B,
-                       before_update=read)
+                       before_update=read, after_forward=after_forward)
         loss = net.loss_sum.item() / B
         assert abs(loss - loss_ref) <= tol * max(abs(loss_ref), 1e-30), f"step {k}: loss {loss} vs {loss_ref}"
         stats["band"] += int(sum(b.sum() for b in bands))
@@ -68,9 +80,10 @@ def run_stepwise_oracle_only(gpu, orc, w, n_steps, tol=1e-4, net=None, oracle_ne
             # a = f(z) is continuous at the kink: every activation is compared without allowance
             worst = max(worst, close(got["acts"][li], onet.acts[li + 1], tol, tag + " activations", mag=mags[li]))
             x_mag = np.abs(onet.acts[0]) if li == 0 else mags[li - 1]
-            mg, mgb, mgx = abs_backward(orc, O, x_mag, mag_dz, need_input_grad=li > 0)
+            val0, vel0, bias0, bvel0 = before[li]                # the backward pass saw the weights before the update
+            mg, mgb, mgx = abs_backward(orc, O, x_mag, mag_dz, need_input_grad=li > 0, val=val0)
             if allow_dz.any():
-                ag, agb, agx = abs_backward(orc, O, x_mag, allow_dz, need_input_grad=li > 0)
+                ag, agb, agx = abs_backward(orc, O, x_mag, allow_dz, need_input_grad=li > 0, val=val0)
             else:
                 ag, agb = np.zeros_like(mg), np.zeros_like(mgb)
                 agx = np.zeros_like(mgx) if mgx is not None else None
@@ -79,7 +92,6 @@ def run_stepwise_oracle_only(gpu, orc, w, n_steps, tol=1e-4, net=None, oracle_ne
             worst = max(worst, close(gb, O.grad_bias, tol, tag + " bias gradient", mag=mgb, allow=agb, tally=stats["tally"][li]))
             _, _, val, vel, bias, bias_vel = G.export_csr()
             lr = float(O.lr)
-            val0, vel0, bias0, bvel0 = before[li]
             worst = max(worst, close(vel, O.vel, tol, tag + " velocities", mag=np.abs(vel0) + lr * mg, allow=lr * ag))
             worst = max(worst, close(val, O.val, tol, tag + " weights", mag=np.abs(val0) + np.abs(vel0) + lr * mg,
                                      allow=lr * ag))
@@ -90,7 +102,9 @@ def run_stepwise_oracle_only(gpu, orc, w, n_steps, tol=1e-4, net=None, oracle_ne
             if li > 0:
                 below = olayers[li - 1]
                 allow_dz = kink_delta(below, bands[li - 1], mgx, agx)
-                mag_dz = mgx * slope_magnitude(below)
+                slope = slope_magnitude(below)
+                slope[bands[li - 1]] = 1.0                 # in the band either branch may have been taken
+                mag_dz = mgx * slope
         stats["steps"] += 1
         stats["worst"] = max(stats["worst"], worst)
         if log and (k % 50 == 0 or k == n_steps - 1):

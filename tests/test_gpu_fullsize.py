@@ -3,7 +3,13 @@ bench.py times (B = 128, all four layers on one GPU), against digests and sample
 tests/golden/make_1m_golden.py computed with the CPU oracle alone.  Topology, indices and fresh
 weights are compared bit for bit over ALL entries (sha256); fp32 tensors on sampled neurons and
 every 8192nd connection, within 1e-4 of the tensor's largest oracle magnitude after the first step and
-within 1e-3 after four steps."""
+within 1e-3 after four and after sixteen steps.
+
+The last tests run the oracle itself at full size next to the GPU (it shares its rows among the host's cores;
+results do not depend on the thread count): four minibatches, each from the ORACLE's state, with every
+activation, gradient, weight and velocity of all 5.3 * 10^7 connections compared element by element at 1e-4; then
+the prune / regrow cycle of Algorithm 2 from the oracle's TRAINED state (non-zero velocities, trained magnitudes),
+in both prune modes, bit for bit over all entries."""
 import hashlib
 import json
 import os
@@ -12,6 +18,7 @@ import numpy as np
 import pytest
 
 from paper_2102_01732_amd import workloads as wl
+from stepwise import make_oracle_net, run_stepwise_oracle_only
 
 pytestmark = pytest.mark.gpu
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "set_mlp_1m_step.json")
@@ -121,4 +128,92 @@ def test_one_million_neuron_four_training_steps(setup):
         near(val[idx], g["val"], g["val_absmax"], 1e-3, f"layer {li} weights after {steps} steps")
         near(vel[idx], g["vel"], g["vel_absmax"], 1e-3, f"layer {li} velocities after {steps} steps")
         near(bias[np.asarray(s1["step"]["rows"])], g["bias"], g["bias_absmax"], 1e-3, f"layer {li} biases after {steps} steps")
+    net.close()
+
+
+def test_one_million_neuron_sixteen_training_steps(setup):
+    """Sixteen steps of the loop that bench.py times, against the oracle's state after the same sixteen steps."""
+    import torch
+    binding, golden, w = setup
+    after = golden["after_more_steps"]
+    steps, B = after["steps"], w.batch
+    X, y = wl.dataset(w, steps * B)
+    blocks = torch.from_numpy(wl.to_batch_blocks(X, B)).cuda()
+    yd = torch.from_numpy(y).cuda()
+    net = make_net(binding, w)
+    losses = []
+    for k in range(steps):
+        net.loss_sum.zero_()
+        net.train_step(blocks[k], yd[k * B:(k + 1) * B], B)
+        losses.append(net.loss_sum.item() / B)
+    for k, (got, ref) in enumerate(zip(losses, after["loss_means"])):
+        assert abs(got - ref) <= 1e-3 * abs(ref), f"loss of step {k + 1}: {got} vs {ref}"
+    stride = golden["val_stride"]
+    for li, (G, g, s1) in enumerate(zip(net.layers, after["layers"], golden["layers"])):
+        idx = np.arange(0, G.nnz, stride)
+        _, _, val, vel, bias, _ = G.export_csr()
+        near(val[idx], g["val"], g["val_absmax"], 1e-3, f"layer {li} weights after {steps} steps")
+        near(vel[idx], g["vel"], g["vel_absmax"], 1e-3, f"layer {li} velocities after {steps} steps")
+        near(bias[np.asarray(s1["step"]["rows"])], g["bias"], g["bias_absmax"], 1e-3, f"layer {li} biases after {steps} steps")
+    net.close()
+
+
+LIVE_STEPS = 4
+_live = {}
+
+
+def live_state(setup, oracle):
+    """The oracle's one-million-neuron network and the GPU network that follows it (built once per session)."""
+    if not _live:
+        binding, _, w = setup
+        print("oracle: initialising 5.3e7 connections ...", flush=True)
+        _live["oracle_net"] = make_oracle_net(oracle, w)
+        _live["net"] = make_net(binding, w)
+        _live["done"] = 0
+    return _live
+
+
+@pytest.mark.parametrize("step", range(LIVE_STEPS))
+def test_one_million_neuron_minibatch_from_the_oracles_state(setup, oracle, step):
+    binding, _, w = setup
+    st = live_state(setup, oracle)
+    if st["done"] > step:
+        pytest.skip("already covered")
+    _, _, _, stats = run_stepwise_oracle_only(binding, oracle, w, step + 1, net=st["net"], oracle_net=st["oracle_net"],
+                                              first_step=st["done"], oracle_logits=True)
+    st["done"] = step + 1
+    for t in stats["tally"]:
+        assert t["needed"] <= 1e-3 * t["checked"], stats
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_one_million_neuron_evolution_of_the_trained_network(setup, oracle, mode):
+    """Algorithm 2's prune / regrow cycle applied to the oracle's state after LIVE_STEPS training steps, on both
+    sides; every array of every layer must come out identical."""
+    binding, _, w = setup
+    st = live_state(setup, oracle)
+    if st["done"] < LIVE_STEPS:       # run alone: train the oracle first (no comparison needed here)
+        X, y = wl.dataset(w, LIVE_STEPS * w.batch)
+        blocks = wl.to_batch_blocks(X, w.batch)
+        for k in range(st["done"], LIVE_STEPS):
+            st["oracle_net"][0].train_step(blocks[k], y[k * w.batch:(k + 1) * w.batch])
+        st["done"] = LIVE_STEPS
+    onet, olayers = st["oracle_net"]
+    net = binding.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=w.batch,
+                            prune_mode=mode)
+    for li, (G, O) in enumerate(zip(net.layers, olayers)):
+        assert np.count_nonzero(O.vel) > 0.9 * O.nnz
+        G.import_csr(O.rowptr, O.colidx, O.val, O.vel, O.bias, O.bias_vel)
+        E = oracle.OracleLayer.__new__(oracle.OracleLayer)
+        E.__dict__.update(O.__dict__)
+        E.set_state(O.rowptr, O.colidx, O.val, O.vel, O.bias, O.bias_vel)
+        E.prune_mode = mode
+        print(f"mode {mode} layer {li}: oracle evolve ...", flush=True)
+        k = E.evolve(w.zeta, 1)
+        G.evolve(w.zeta, 1)
+        rowptr, colidx, val, vel, _, _ = G.export_csr()
+        assert G.nnz == O.nnz and abs(k - w.zeta * O.nnz) <= 1
+        assert np.array_equal(rowptr, E.rowptr) and np.array_equal(colidx, E.colidx), f"layer {li} pattern"
+        assert np.array_equal(val.view(np.uint32), E.val.view(np.uint32)), f"layer {li} weights"
+        assert np.array_equal(vel.view(np.uint32), E.vel.view(np.uint32)), f"layer {li} velocities"
     net.close()
