@@ -92,6 +92,19 @@ int sparse_layer_forward(sl_layer *layer, const float *x_dev, int64_t ldx, int32
 int sparse_layer_infer(sl_layer *layer, const float *x_dev, int64_t ldx, int32_t B, float *a_dev, int64_t lda,
                        void *hip_stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace at call time (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): sparse_layer_infer with the partial sums of
+ * split rows kept in a buffer of SL_STATIC_SCRATCH_MIB MiB that is built into the library (one copy per GPU,
+ * held until the process ends) instead of in the layer's scratch buffer.  Same arguments, same results bit for
+ * bit.  Allocates nothing and creates no events.  SL_ENOMEM if the layer's partial sums (virtual rows x
+ * round_up(max_batch, 32) floats; zero for layers without split rows) do not fit, SL_ESTATE while per-kernel
+ * profiling is on.  The device of `hip_stream` must be current.  All calls on one GPU share that GPU's buffer:
+ * calls that overlap in time on one GPU (two streams, two threads) race; nothing in it needs clearing between
+ * calls.  Asynchronous. */
+#define SL_STATIC_SCRATCH_MIB 16
+int sparse_layer_infer_static(sl_layer *layer, const float *x_dev, int64_t ldx, int32_t B, float *a_dev, int64_t lda,
+                              void *hip_stream);
+
 /* Backward of the same minibatch (must follow forward with the same B):
  *   dz = grad_a * f_l'(z)                     (f' at z = 0 is the "z <= 0" branch of eq. 3)
  *   grad_bias[j] = sum_b dz[j][b]

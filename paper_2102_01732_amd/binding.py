@@ -28,7 +28,7 @@ EXPORTS = [
     "sparse_kernel_name", "sparse_layer_link_producer", "sparse_layer_importance", "sparse_layer_importance_prune",
     "sparse_layer_infer", "sparse_layers_average_query", "sparse_layers_average",
     "sparse_loss_softmax_ce_into", "sparse_layers_update", "sparse_layer_set_dropout",
-    "sparse_layer_retain_valid_updates",
+    "sparse_layer_retain_valid_updates", "sparse_layer_infer_static",
 ]
 N_KERNEL_IDS = 7
 
@@ -60,6 +60,7 @@ def lib():
         L.sparse_layer_init.argtypes = [C.POINTER(SlConfig), vp, C.c_size_t, vp, C.c_size_t, vp, C.POINTER(vp)]
         L.sparse_layer_forward.argtypes = [vp, f32p, i64, i32, f32p, i64, vp]
         L.sparse_layer_infer.argtypes = [vp, f32p, i64, i32, f32p, i64, vp]
+        L.sparse_layer_infer_static.argtypes = [vp, f32p, i64, i32, f32p, i64, vp]
         L.sparse_layer_backward.argtypes = [vp, f32p, i64, f32p, i64, i32, f32p, i64, vp]
         L.sparse_layer_update.argtypes = [vp, vp]
         L.sparse_layer_evolve.argtypes = [vp, C.c_double, C.c_uint64, vp]
@@ -149,6 +150,10 @@ class SparseLayer:
     def infer(self, x: torch.Tensor, B: int, a: torch.Tensor):
         self._check(lib().sparse_layer_infer(self.handle, x.data_ptr(), x.stride(0), B, a.data_ptr(), a.stride(0),
                                              _stream()), "sparse_layer_infer")
+
+    def infer_static(self, x: torch.Tensor, B: int, a: torch.Tensor):
+        self._check(lib().sparse_layer_infer_static(self.handle, x.data_ptr(), x.stride(0), B, a.data_ptr(), a.stride(0),
+                                                    _stream()), "sparse_layer_infer_static")
 
     def set_dropout(self, p: float, step: int):
         self._check(lib().sparse_layer_set_dropout(self.handle, float(p), int(step)), "sparse_layer_set_dropout")

@@ -234,6 +234,7 @@ int sparse_layer_init(const sl_config *cfg, void *state_dev, size_t state_bytes,
     hipStream_t s = (hipStream_t)hip_stream;
     L->last_stream = s;
     rc = topo_init(L, s);
+    if (rc == SL_OK) rc = static_scratch_setup(L, nullptr);   // address of the built-in buffer on this device
     if (rc == SL_OK) {
         hipError_t e = hipStreamSynchronize(s);
         if (e != hipSuccess) rc = SL_EHIP;
@@ -284,6 +285,19 @@ int sparse_layer_infer(sl_layer *L, const float *x_dev, int64_t ldx, int32_t B, 
     if (rc) return rc;
     L->last_stream = (hipStream_t)hip_stream;
     return launch_forward(L, x_dev, ldx, B, a_dev, lda, false, L->last_stream);
+}
+
+int sparse_layer_infer_static(sl_layer *L, const float *x_dev, int64_t ldx, int32_t B, float *a_dev, int64_t lda,
+                              void *hip_stream)
+{
+    if (!L) return SL_EINVAL;
+    if (B <= 0 || B > L->cfg.max_batch) return set_err(L, SL_EINVAL, "B = %d outside 1..max_batch = %d", B, L->cfg.max_batch);
+    int rc = check_dense(L, x_dev, ldx, B, "x");
+    if (rc) return rc;
+    rc = check_dense(L, a_dev, lda, B, "a");
+    if (rc) return rc;
+    L->last_stream = (hipStream_t)hip_stream;
+    return launch_forward_static(L, x_dev, ldx, B, a_dev, lda, L->last_stream);
 }
 
 int sparse_layer_set_dropout(sl_layer *L, float p, uint64_t step)

@@ -155,7 +155,10 @@ int64_t sampler_window(double M, double n_occ, double k);
 int choose_seg(int64_t n_rows, int64_t nnz);
 
 // training kernels (sl_train.hip)
-int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, int64_t lda, bool save_sign, hipStream_t s);
+int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, int64_t lda, bool save_sign, hipStream_t s,
+                   float *part = nullptr);   // part: where a split matrix puts its partial sums (null: the layer's scratch)
+int launch_forward_static(sl_layer *L, const float *x, int64_t ldx, int B, float *a, int64_t lda, hipStream_t s);
+int static_scratch_setup(sl_layer *L, void **ptr);
 int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, int64_t ldg, int B, float *gx,
                     int64_t ldgx, hipStream_t s);
 int launch_update(sl_layer *L, hipStream_t s);

@@ -12,6 +12,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <mutex>
 #include <type_traits>
 #include <utility>
 
@@ -827,10 +828,11 @@ static Epi dz_epilogue(sl_layer *owner, int B)
     return e;
 }
 
-static void launch_fix(sl_layer *L, const SegMat &m, const Epi &epi, int G, int kernel_id, hipStream_t s)
+static void launch_fix(sl_layer *L, const SegMat &m, const Epi &epi, int G, int kernel_id, hipStream_t s,
+                       const float *part = nullptr)
 {
     FixArgs fx;
-    fx.rvptr = m.rvptr; fx.n_rows = m.n_rows; fx.part = (const float *)(L->scratch + L->cp.partial); fx.ldp = L->ldz;
+    fx.rvptr = m.rvptr; fx.n_rows = m.n_rows; fx.part = part ? part : (const float *)(L->scratch + L->cp.partial); fx.ldp = L->ldz;
     fx.epi = epi;
     ProfScope ps(L, kernel_id, s);
     dispatch_g(G, [&](auto g) {
@@ -840,7 +842,8 @@ static void launch_fix(sl_layer *L, const SegMat &m, const Epi &epi, int G, int 
     });
 }
 
-int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, int64_t lda, bool save_sign, hipStream_t s)
+int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, int64_t lda, bool save_sign, hipStream_t s,
+                   float *part)
 {
     const SegMat &m = L->fwd;
     const int G = group_width(B), U = chunk_width(m, L->nnz);
@@ -850,7 +853,8 @@ int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, in
     // every row of a fully dense matrix has the same length, hence the same number of equal runs
     const bool dense = m.split && L->nnz == L->cfg.n_in * L->cfg.n_out && m.nv % m.n_rows == 0;
     f.twin_rows = dense && m.n_rows > 1 ? m.n_rows : 0;
-    f.part = m.split ? (float *)(L->scratch + L->cp.partial) : nullptr; f.ldp = L->ldz;
+    if (!part) part = (float *)(L->scratch + L->cp.partial);
+    f.part = m.split ? part : nullptr; f.ldp = L->ldz;
     Epi &e = f.epi;
     e.mode = EPI_FWD; e.out = a; e.ldo = lda; e.bias = L->bias; e.mask_w = save_sign ? L->mask : nullptr; e.mask_r = nullptr; e.ldm = L->ldm;
     e.gb = nullptr; e.act_kind = L->cfg.act_kind; e.slope = L->cfg.act_parity == 0 ? -L->cfg.alpha : L->cfg.alpha; e.B = B;
@@ -871,9 +875,56 @@ int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, in
             });
         }
     }
-    if (m.split) launch_fix(L, m, e, G, K_FWD_FIX, s);
+    if (m.split) launch_fix(L, m, e, G, K_FWD_FIX, s, part);
     SL_HIP(L, hipGetLastError());
     return SL_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Forward pass whose partial sums live in a buffer that is part of the library's code object instead of
+// the caller's scratch buffer (sparse_layer_infer_static): for callers that cannot allocate.  Every GPU
+// holds its own copy of the array at its own address; `scratch` below is only the host-side name of the
+// symbol, and the address that kernels and copies may use is the one hipGetSymbolAddress returns on that
+// device.
+// ------------------------------------------------------------------------------------------------
+static constexpr size_t STATIC_SCRATCH_BYTES = (size_t)SL_STATIC_SCRATCH_MIB << 20;
+static constexpr int STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+static std::mutex static_mu;
+static void *static_ptr[STATIC_MAX_DEVICES] = {};
+
+// Looks the array up on the current device (once per device).  Called from sparse_layer_init, so that the
+// forward call itself finds the address ready, and again from the forward call in case the layer was
+// created while another device was current.
+int static_scratch_setup(sl_layer *L, void **ptr)
+{
+    int dev = -1;
+    SL_HIP(L, hipGetDevice(&dev));
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) return set_err(L, SL_EINVAL, "device ordinal %d not supported", dev);
+    std::lock_guard<std::mutex> lock(static_mu);
+    if (!static_ptr[dev]) {
+        void *p = nullptr;
+        SL_HIP(L, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return set_err(L, SL_EHIP, "hipGetSymbolAddress returned a null address");
+        static_ptr[dev] = p;
+    }
+    if (ptr) *ptr = static_ptr[dev];
+    return SL_OK;
+}
+
+int launch_forward_static(sl_layer *L, const float *x, int64_t ldx, int B, float *a, int64_t lda, hipStream_t s)
+{
+    if (L->prof_on) return set_err(L, SL_ESTATE, "infer_static: per-kernel profiling creates events; end it first");
+    const SegMat &m = L->fwd;
+    const size_t need = m.split ? sizeof(float) * (size_t)m.nv * (size_t)L->ldz : 0;
+    if (need > STATIC_SCRATCH_BYTES)
+        return set_err(L, SL_ENOMEM, "infer_static: %zu bytes of partial sums exceed the built-in buffer of %zu bytes", need,
+                       STATIC_SCRATCH_BYTES);
+    void *p = nullptr;
+    int rc = static_scratch_setup(L, &p);
+    if (rc) return rc;
+    // nothing has to start at zero: the SpMM kernel writes every partial sum that the fix-up kernel reads
+    return launch_forward(L, x, ldx, B, a, lda, false, s, (float *)p);
 }
 
 // Batches above 256 columns take two tiles per pass with half the chunk width (the same number of row
