@@ -139,6 +139,16 @@ int sparse_layer_link_producer(sl_layer *layer, sl_layer *producer);
  * vel <- mu*vel - eta*(grad + weight_decay*w);  w <- w + vel.  Must follow backward.  Asynchronous. */
 int sparse_layer_update(sl_layer *layer, void *hip_stream);
 
+/* Update fused behind the SDDMM (eq. 1 applied where Algorithm 1's worker gradient of a connection is
+ * produced).  mode 0 (default): sparse_layer_backward stores the weight gradient and sparse_layer_update applies
+ * eq. (1).  mode 1: sparse_layer_backward itself applies eq. (1) to every stored connection in the kernel that
+ * finishes its gradient entry (same fp32 arithmetic, same result bit for bit) and does not store the gradient
+ * (sparse_layer_export_grad then returns SL_ESTATE for grad_val); sparse_layer_update / sparse_layers_update must
+ * still follow and update the biases only.  mode 2: as mode 1, and the gradient is stored as well.  The weights
+ * that backward uses for the input gradient are those before the update in every mode.  SL_ESTATE between
+ * backward and update. */
+int sparse_layer_set_fused_update(sl_layer *layer, int32_t mode);
+
 /* Algorithm 2's weight pruning-regrowing cycle: removes k connections (see prune_mode), draws k
  * distinct empty positions with the Philox sampler at `generation` (>= 1, < 2^32; a different
  * value per call), gives them fresh weights and zero velocity, and rebuilds CSR and the CSC

@@ -29,6 +29,7 @@ EXPORTS = [
     "sparse_layer_infer", "sparse_layers_average_query", "sparse_layers_average",
     "sparse_loss_softmax_ce_into", "sparse_layers_update", "sparse_layer_set_dropout",
     "sparse_layer_retain_valid_updates", "sparse_layer_infer_static",
+    "sparse_layer_set_fused_update",
 ]
 N_KERNEL_IDS = 7
 
@@ -63,6 +64,7 @@ def lib():
         L.sparse_layer_infer_static.argtypes = [vp, f32p, i64, i32, f32p, i64, vp]
         L.sparse_layer_backward.argtypes = [vp, f32p, i64, f32p, i64, i32, f32p, i64, vp]
         L.sparse_layer_update.argtypes = [vp, vp]
+        L.sparse_layer_set_fused_update.argtypes = [vp, i32]
         L.sparse_layer_evolve.argtypes = [vp, C.c_double, C.c_uint64, vp]
         L.sparse_layer_destroy.argtypes = [vp]
         L.sparse_loss_softmax_ce.argtypes = [f32p, i64, i32p, i32, i32, f32p, i64, f32p, vp]
@@ -171,6 +173,11 @@ class SparseLayer:
 
     def update(self):
         self._check(lib().sparse_layer_update(self.handle, _stream()), "sparse_layer_update")
+
+    def set_fused_update(self, mode: int):
+        """0: backward stores the gradient, update applies eq. (1); 1: backward applies it to the connections itself
+        (gradient not stored), update finishes the biases; 2: as 1, gradient stored as well."""
+        self._check(lib().sparse_layer_set_fused_update(self.handle, int(mode)), "sparse_layer_set_fused_update")
 
     def evolve(self, zeta: float, generation: int):
         self._check(lib().sparse_layer_evolve(self.handle, float(zeta), int(generation), _stream()),
@@ -303,6 +310,8 @@ class SparseMLP:
         self._handles = (C.c_void_p * len(self.layers))(*[l.handle for l in self.layers])
         self.loss_sum = torch.zeros(1, dtype=torch.float32, device=self.device)
         self.n_classes = layer_specs[-1].n_out
+        self.fused_update = 0       # train_step: 0 = one update launch for all layers (faster, see set_fused_update), 1 = eq. (1) inside the backward kernels
+        self._fuse_mode = 0
         self.dropout = 0.0          # rate applied to the hidden layers by train_step (0 = off)
         self.step_index = 0         # selects the dropout masks; advanced by train_step
 
@@ -337,6 +346,12 @@ class SparseMLP:
             for layer in self.layers[:-1]:
                 layer.set_dropout(self.dropout, self.step_index)
         self.step_index += 1
+        # with fused_update = 1 eq. (1) is applied inside the backward kernels, unless somebody wants to look at the gradients first
+        mode = self.fused_update if before_update is None else 0
+        if mode != self._fuse_mode:
+            for layer in self.layers:
+                layer.set_fused_update(mode)
+            self._fuse_mode = mode
         zL = self.forward(x, B)
         if after_forward is not None:
             after_forward(self)

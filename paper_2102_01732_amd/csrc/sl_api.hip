@@ -368,6 +368,16 @@ int sparse_layer_update(sl_layer *L, void *hip_stream)
     int rc = launch_update(L, L->last_stream);
     if (rc) return rc;
     L->phase = 0;
+    L->weights_updated = false;
+    return SL_OK;
+}
+
+int sparse_layer_set_fused_update(sl_layer *L, int32_t mode)
+{
+    if (!L) return SL_EINVAL;
+    if (mode < 0 || mode > 2) return set_err(L, SL_EINVAL, "fused update mode %d outside 0..2", mode);
+    if (L->phase == 2) return set_err(L, SL_ESTATE, "set_fused_update between backward and update");
+    L->fuse_mode = mode;
     return SL_OK;
 }
 
@@ -382,6 +392,7 @@ int sparse_layer_evolve(sl_layer *L, double zeta, uint64_t generation, void *hip
     hipError_t e = hipStreamSynchronize(L->last_stream);
     if (e != hipSuccess) return set_err(L, SL_EHIP, "evolve: %s", hipGetErrorString(e));
     L->phase = 0;
+    L->weights_updated = false;
     return SL_OK;
 }
 
@@ -401,6 +412,8 @@ int sparse_layer_retain_valid_updates(sl_layer *L, const int32_t *old_rowptr_dev
                              L->last_stream));
     L->phase = 2;
     L->dz_ready = 0;
+    L->weights_updated = false;
+    L->grad_stored = true;
     return SL_OK;
 }
 
@@ -545,6 +558,7 @@ int sparse_layers_update(sl_layer *const *layers, int32_t count, void *hip_strea
     if (rc) return rc;
     for (int k = 0; k < count; ++k) {
         layers[k]->phase = 0;
+        layers[k]->weights_updated = false;
         layers[k]->last_stream = s;
     }
     return SL_OK;
@@ -610,6 +624,7 @@ int sparse_layer_import_csr(sl_layer *L, const int32_t *rowptr, const int32_t *c
     if (rc) return rc;
     SL_HIP(L, hipStreamSynchronize(s));
     L->phase = 0;
+    L->weights_updated = false;
     return SL_OK;
 }
 
@@ -617,6 +632,7 @@ int sparse_layer_export_grad(sl_layer *L, float *grad_val, float *grad_bias)
 {
     if (!L) return SL_EINVAL;
     if (L->phase < 2) return set_err(L, SL_ESTATE, "no gradient: backward has not run since the last update");
+    if (grad_val && !L->grad_stored) return set_err(L, SL_ESTATE, "no gradient: the fused update (mode 1) does not store it");
     const size_t n = (size_t)L->nnz, no = (size_t)L->cfg.n_out;
     int rc = SL_OK;
     if (grad_val && n > 0) {

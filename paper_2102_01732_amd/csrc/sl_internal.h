@@ -95,6 +95,11 @@ struct sl_layer {
     // dropout on this layer's activations for the next forward/backward pair (0 = off)
     uint32_t drop_thr = 0, drop_step = 0;
     float drop_scale = 1.f;
+    // Update fused behind the SDDMM: 0 off, 1 backward applies eq. (1) to the connections and does not store
+    // the gradient, 2 applies it and stores the gradient as well.  weights_updated / grad_stored describe the
+    // pending backward pass (phase 2).
+    int fuse_mode = 0;
+    bool weights_updated = false, grad_stored = true;
     int phase = 0;     // 0 idle, 1 forward done, 2 backward done
     int last_B = 0;
     hipStream_t last_stream = nullptr;

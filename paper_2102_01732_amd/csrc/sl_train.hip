@@ -93,6 +93,18 @@ __device__ __forceinline__ void store_row4(float *row, int c, int B, float4 v)
     }
 }
 
+// Momentum SGD, eq. (1) in velocity form, for one connection.  The products are rounded separately (no
+// fused multiply-add) so that the result is the plain fp32 evaluation of
+// vel = mu*vel - eta*(g + lambda*w);  w = w + vel.
+__device__ __forceinline__ void update_one(float &w, float &vel, float g, float lr, float mu, float wd)
+{
+#pragma clang fp contract(off)   // separate roundings: this must equal the plain fp32 evaluation
+    const float gg = g + wd * w;
+    const float vn = mu * vel - lr * gg;
+    vel = vn;
+    w = w + vn;
+}
+
 // ------------------------------------------------------------------------------------------------
 // What happens to a finished row of accumulators.
 //   EPI_FWD   : + bias, All-ReLU (eq. 3), sign mask of z saved for backward      -> a
@@ -369,7 +381,33 @@ struct BwdArgs {
     int ragged;      // B % 4 != 0
     int tile0, tile1; // bwd_pair_kernel: the batch tiles this launch covers
     Epi epi;         // SPMM, not split: what to do with the finished grad_x row
+    // Update fused behind the SDDMM (eq. 1 applied where the gradient entry is produced): on the last batch
+    // tile the lane that holds a finished gradient entry also holds (or fetches) that connection's weight
+    // and velocity, so it writes the new velocity and weight instead of the gradient.  upd_mode 0: off (the
+    // gradient is stored), 1: update, gradient not stored, 2: update and store the gradient.
+    int upd_mode;
+    int n_tiles;     // batch tiles of the whole call (the update happens on the last one)
+    float *upd_w, *upd_vel;      // master weights / velocities in the order of this orientation
+    const int *upd_pos;          // CSC slot -> CSR slot of the weight copy read by forward (null: none)
+    float *upd_w_csr;
+    float lr, mu, wd;
 };
+
+// What the lane that finished gradient entry q does with it.  w: the connection's weight before the update where the
+// caller holds it (the SPMM form: a writer lane's own entry is entry `lane` of its chunk).  The update's other
+// operands are fetched here, after the chunk's row gathers have been consumed, so that they occupy no register
+// while those gathers are in flight (one register more there costs the fused backward a wave of occupancy).
+template <bool UPD, bool HAVE_W>
+__device__ __forceinline__ void store_entry(const BwdArgs &a, unsigned q, float gval, bool last_tile, float w, float v, unsigned pos)
+{
+    if (!UPD || !last_tile) { a.g[q] = gval; return; }
+    if (!HAVE_W) w = a.upd_w[q];
+    update_one(w, v, gval, a.lr, a.mu, a.wd);
+    a.upd_vel[q] = v;
+    a.upd_w[q] = w;
+    if (a.upd_pos) a.upd_w_csr[pos] = w;
+    if (a.upd_mode == 2) a.g[q] = gval;
+}
 
 template <int G, int U>
 __device__ __forceinline__ float reduce_chunk(float (&s)[U], int lane)
@@ -400,7 +438,7 @@ __device__ __forceinline__ float reduce_chunk(float (&s)[U], int lane)
 // while the current chunk's row gathers are in flight at a cost of two registers.  The gathered
 // operand of the SPMM form is the library's own dz, whose columns past B are zero; the caller's x
 // (gathered by the SDDMM form, held by the SPMM form) may hold anything there and is clipped.
-template <int G, int U, bool SPMM>
+template <int G, int U, bool SPMM, bool UPD>
 __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
 {
     const int lane = threadIdx.x % G;
@@ -412,6 +450,7 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
     for (int tile = 0; tile * 4 * G < a.B; ++tile) {
         const int c = (tile * G + lane) * 4;
         const bool active = c < a.B;
+        const bool upd = UPD && tile + 1 == a.n_tiles;   // last batch tile: the gradient entries are final
         const int cg = active ? c : 0;   // idle lanes gather columns 0..3 and multiply them by a zero h
         float4 h = zero4();
         if (active) {
@@ -437,8 +476,13 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
             // later batch tiles add to what the earlier ones stored; fetch it with the indices, not after
             // the reduction, so that its latency hides behind the row gathers
             const bool writer = lane < U && p + lane < p1;
-            float g_prev = 0.f;
+            float g_prev = 0.f, vel_prev = 0.f;
+            unsigned pos = 0;
             if (tile > 0 && writer) g_prev = a.g[p + lane];
+            if (UPD && upd && writer) {   // the update's own operands travel with the indices
+                vel_prev = a.upd_vel[(unsigned)(p + lane)];
+                if (a.upd_pos) pos = (unsigned)a.upd_pos[(unsigned)(p + lane)];
+            }
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
                 const int cc = chunk_entry<G, u>(my_c);
@@ -458,7 +502,7 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
                 s[u] = fmaf(h.x, xv[u].x, fmaf(h.y, xv[u].y, fmaf(h.z, xv[u].z, h.w * xv[u].w)));
             });
             const float r = reduce_chunk<G, U>(s, lane);
-            if (writer) a.g[p + lane] = g_prev + r;
+            if (writer) store_entry<UPD, SPMM>(a, (unsigned)(p + lane), g_prev + r, upd, my_w, vel_prev, pos);
             my_c = nx_c;
             my_w = nx_w;
         }
@@ -477,7 +521,7 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
 // row, the two tiles' products are added before the cross-lane reduction, and the per-entry gradient is
 // written once per pair of tiles instead of once per tile.  (Kept apart from bwd_kernel: folding the two
 // into one template cost the single-tile instances twelve registers and one wave of occupancy.)
-template <int U, bool SPMM>
+template <int U, bool SPMM, bool UPD>
 __global__ __launch_bounds__(BLOCK) void bwd_pair_kernel(BwdArgs a)
 {
     constexpr int G = 64, T = 2;
@@ -491,6 +535,7 @@ __global__ __launch_bounds__(BLOCK) void bwd_pair_kernel(BwdArgs a)
         int c[T], cg[T];
         bool active[T];
         float4 h[T], acc[T];
+        const bool upd = UPD && tile + T >= a.n_tiles;   // the pair that holds the last batch tile
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             c[t] = ((tile + t) * G + lane) * 4;
@@ -520,8 +565,13 @@ __global__ __launch_bounds__(BLOCK) void bwd_pair_kernel(BwdArgs a)
             // later tile pairs add to what the earlier ones stored; fetch it with the indices, not after the
             // reduction, so that its latency hides behind the row gathers
             const bool writer = lane < U && p + lane < p1;
-            float g_prev = 0.f;
+            float g_prev = 0.f, vel_prev = 0.f;
+            unsigned pos = 0;
             if (tile > 0 && writer) g_prev = a.g[p + lane];
+            if (UPD && upd && writer) {
+                vel_prev = a.upd_vel[(unsigned)(p + lane)];
+                if (a.upd_pos) pos = (unsigned)a.upd_pos[(unsigned)(p + lane)];
+            }
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
                 const float *src = a.gath + (long)chunk_entry<G, u>(my_c) * a.ldga;
@@ -552,7 +602,7 @@ __global__ __launch_bounds__(BLOCK) void bwd_pair_kernel(BwdArgs a)
                 s[u] = d;
             });
             const float r = reduce_chunk<G, U>(s, lane);
-            if (writer) a.g[p + lane] = g_prev + r;
+            if (writer) store_entry<UPD, SPMM>(a, (unsigned)(p + lane), g_prev + r, upd, my_w, vel_prev, pos);
             my_c = nx_c;
             my_w = nx_w;
         }
@@ -650,14 +700,6 @@ struct UpdateOne {
     const float *gbias;
     float lr, mu, wd;
 };
-__device__ __forceinline__ void update_one(float &w, float &vel, float g, float lr, float mu, float wd)
-{
-#pragma clang fp contract(off)   // separate roundings: this must equal the plain fp32 evaluation
-    const float gg = g + wd * w;
-    const float vn = mu * vel - lr * gg;
-    vel = vn;
-    w = w + vn;
-}
 // Thread t of a layer takes the four connections 4t .. 4t+3 (16-byte loads and stores of the three streams;
 // the state arrays are 256-byte aligned), the threads after ceil(n/4) take one bias each.
 __device__ __forceinline__ void update_thread(const UpdateOne &u, long t)
@@ -927,10 +969,8 @@ int launch_forward_static(sl_layer *L, const float *x, int64_t ldx, int B, float
     return launch_forward(L, x, ldx, B, a, lda, false, s, (float *)p);
 }
 
-// Batches above 256 columns take two tiles per pass with half the chunk width (the same number of row
-// gathers in flight per lane).
-template <bool SPMM>
-static void launch_bwd_kernel(int G, int U, int B, int nv, BwdArgs b, hipStream_t s)
+template <bool SPMM, bool UPD>
+static void launch_bwd_kernel_u(int G, int U, int B, int nv, BwdArgs b, hipStream_t s)
 {
     b.tile0 = 0;
     b.tile1 = (B + 4 * G - 1) / (4 * G);
@@ -942,21 +982,35 @@ static void launch_bwd_kernel(int G, int U, int B, int nv, BwdArgs b, hipStream_
         const dim3 grid(groups_to_blocks(nv, 64));
         const int tiles = b.tile1;
         if (U < 4) {
-            hipLaunchKernelGGL((bwd_pair_kernel<2, SPMM>), grid, dim3(BLOCK), 0, s, b);
+            hipLaunchKernelGGL((bwd_pair_kernel<2, SPMM, UPD>), grid, dim3(BLOCK), 0, s, b);
             return;
         }
         for (int t0 = 0; t0 < tiles; t0 += 2) {
             b.tile0 = t0;
             b.tile1 = min(t0 + 2, tiles);
-            if (U >= 8) hipLaunchKernelGGL((bwd_pair_kernel<4, SPMM>), grid, dim3(BLOCK), 0, s, b);
-            else hipLaunchKernelGGL((bwd_pair_kernel<2, SPMM>), grid, dim3(BLOCK), 0, s, b);
+            // only the launch that holds the last tile sees finished gradient entries
+            if (UPD && b.tile1 == tiles) {
+                if (U >= 8) hipLaunchKernelGGL((bwd_pair_kernel<4, SPMM, UPD>), grid, dim3(BLOCK), 0, s, b);
+                else hipLaunchKernelGGL((bwd_pair_kernel<2, SPMM, UPD>), grid, dim3(BLOCK), 0, s, b);
+            } else {
+                if (U >= 8) hipLaunchKernelGGL((bwd_pair_kernel<4, SPMM, false>), grid, dim3(BLOCK), 0, s, b);
+                else hipLaunchKernelGGL((bwd_pair_kernel<2, SPMM, false>), grid, dim3(BLOCK), 0, s, b);
+            }
         }
         return;
     }
     dispatch_gu(G, U, [&](auto g, auto u) {
         constexpr int GG = decltype(g)::value, UU = decltype(u)::value;
-        hipLaunchKernelGGL((bwd_kernel<GG, UU, SPMM>), dim3(groups_to_blocks(nv, GG)), dim3(BLOCK), 0, s, b);
+        hipLaunchKernelGGL((bwd_kernel<GG, UU, SPMM, UPD>), dim3(groups_to_blocks(nv, GG)), dim3(BLOCK), 0, s, b);
     });
+}
+// Batches above 256 columns take two tiles per pass with half the chunk width (the same number of row
+// gathers in flight per lane).
+template <bool SPMM>
+static void launch_bwd_kernel(int G, int U, int B, int nv, const BwdArgs &b, hipStream_t s)
+{
+    if (b.upd_mode != 0) launch_bwd_kernel_u<SPMM, true>(G, U, B, nv, b, s);
+    else launch_bwd_kernel_u<SPMM, false>(G, U, B, nv, b, s);
 }
 
 int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, int64_t ldg, int B, float *gx,
@@ -976,6 +1030,10 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
     L->dz_ready = 0;
     BwdArgs b;
     b.B = B; b.g = L->grad; b.ragged = (B % 4) != 0; b.part = nullptr; b.ldp = L->ldz;
+    b.upd_mode = L->fuse_mode; b.n_tiles = (B + 4 * G - 1) / (4 * G);
+    b.upd_w = L->has_csc ? L->valT : L->val; b.upd_vel = L->has_csc ? L->velT : L->vel;
+    b.upd_pos = L->has_csc ? L->csr_pos : nullptr; b.upd_w_csr = L->val;
+    b.lr = L->cfg.lr; b.mu = L->cfg.momentum; b.wd = L->cfg.weight_decay;
     if (L->has_csc) {
         const SegMat &m = L->bwd;
         const int U = chunk_width(m, L->nnz);
@@ -1006,13 +1064,16 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
         launch_bwd_kernel<false>(G, U, B, m.nv, b, s);
     }
     SL_HIP(L, hipGetLastError());
+    L->weights_updated = L->fuse_mode != 0;
+    L->grad_stored = L->fuse_mode != 1;
     return SL_OK;
 }
 
 static UpdateOne update_args(const sl_layer *L)
 {
     UpdateOne u;
-    u.n = L->nnz; u.first = 0; u.nb = (int)L->cfg.n_out;
+    // after a backward pass that already applied eq. (1) to the connections only the biases are left
+    u.n = L->weights_updated ? 0 : L->nnz; u.first = 0; u.nb = (int)L->cfg.n_out;
     u.w = L->has_csc ? L->valT : L->val; u.vel = L->has_csc ? L->velT : L->vel; u.g = L->grad;
     u.scatter_pos = L->has_csc ? L->csr_pos : nullptr; u.w_csr = L->has_csc ? L->val : nullptr;
     u.bias = L->bias; u.bias_vel = L->bias_vel; u.gbias = L->grad_bias;

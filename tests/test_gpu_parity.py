@@ -1012,3 +1012,82 @@ def test_training_learns_and_is_reproducible(gpu):
         for u, v in zip(a, b):
             assert np.array_equal(u.view(np.uint32) if u.dtype == np.float32 else u,
                                   v.view(np.uint32) if v.dtype == np.float32 else v)
+
+
+# ------------------------------------------------------------------------------------------ update fused behind the SDDMM
+@pytest.mark.parametrize("n_in,n_out,nnz,B,max_batch,need_gx", [
+    (500, 400, 9000, 128, 128, True), (500, 400, 9000, 128, 128, False),      # CSC-ordered and CSR-ordered (first layer)
+    (300, 700, 6000, 31, 32, True), (256, 300, 4000, 64, 64, False),          # groups of 8 and 16 lanes, ragged
+    (200, 150, 3000, 600, 1024, True), (200, 150, 3000, 1021, 1024, False),   # batch tiles: the update waits for the last one
+    (6, 2000, 12000, 300, 512, True), (400, 2, 800, 128, 128, True),          # split columns / split rows
+    (1500, 2500, 5000, 1000, 1024, True),                                     # very short rows: all tile pairs in one launch
+    (3000, 5000, 37, 128, 128, True)])
+def test_fused_update_equals_separate_update(gpu, n_in, n_out, nnz, B, max_batch, need_gx):
+    """Eq. (1) applied inside the backward kernel (modes 1 and 2) gives the bits of backward followed by the update
+    kernel (mode 0): weights, velocities, the CSR copy that forward reads, biases; and mode 2 also stores the
+    same gradient."""
+    import torch
+    rng = np.random.default_rng(nnz + B)
+    x = dev(torch, rng.standard_normal((n_in, (B + 3) // 4 * 4)).astype(np.float32))
+    ga = dev(torch, rng.standard_normal((n_out, (B + 3) // 4 * 4)).astype(np.float32))
+    out = []
+    for mode in (0, 1, 2):
+        L = gpu.SparseLayer(gpu.make_config(n_in, n_out, nnz=nnz, act_kind=1, act_parity=0, alpha=0.6, init_limit=0.2,
+                                            lr=0.01, momentum=0.9, weight_decay=0.01, seed=8, layer_id=1,
+                                            max_batch=max_batch, need_input_grad=need_gx))
+        rowptr, colidx, val, vel, bias, bias_vel = L.export_csr()
+        vel = (np.random.default_rng(1).standard_normal(nnz) * 0.01).astype(np.float32)
+        L.import_csr(rowptr, colidx, val, vel, bias, bias_vel)
+        L.set_fused_update(mode)
+        a = torch.zeros((n_out, x.shape[1]), device="cuda")
+        gx = torch.zeros((n_in, x.shape[1]), device="cuda") if need_gx else None
+        grads = []
+        for step in range(2):                         # the second step reads the weights the first one wrote
+            L.forward(x, B, a)
+            L.backward(x, ga, B, gx)
+            if mode == 1:
+                with pytest.raises(gpu.SparseSetError) as e:
+                    L.export_grad()
+                assert e.value.code == gpu.SL_ESTATE
+            else:
+                grads.append(L.export_grad())
+            with pytest.raises(gpu.SparseSetError):
+                L.set_fused_update(0)                 # not between backward and update
+            L.update()
+        out.append((L.export_csr(), grads, a.cpu().numpy(), None if gx is None else gx.cpu().numpy()))
+        L.close()
+    ref = out[0]
+    for got in out[1:]:
+        for u, v in zip(ref[0], got[0]):
+            assert np.array_equal(u.view(np.uint32) if u.dtype == np.float32 else u,
+                                  v.view(np.uint32) if v.dtype == np.float32 else v)
+        assert np.array_equal(ref[2], got[2])
+        if need_gx:
+            assert np.array_equal(ref[3], got[3])
+    for (g0, gb0), (g2, gb2) in zip(ref[1], out[2][1]):
+        assert np.array_equal(g0.view(np.uint32), g2.view(np.uint32)) and np.array_equal(gb0.view(np.uint32), gb2.view(np.uint32))
+    assert np.abs(ref[0][3]).max() > 0
+
+
+def test_training_step_with_and_without_fused_update(gpu):
+    """The network loop with the update inside the backward kernels against the same loop with the separate
+    update launch (the default of train_step): identical bits after several steps, ragged last minibatch included."""
+    import torch
+    w = wl.WORKLOADS["set_mlp_madelon"]
+    X, y = wl.dataset(w, 4 * 128 + 77)
+    blocks = dev(torch, wl.to_batch_blocks(X, 128))
+    yd = dev(torch, y)
+    states = []
+    for fused in (0, 1):
+        net = gpu.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=128)
+        net.fused_update = fused
+        for k in range(5):
+            B = min(128, X.shape[0] - k * 128)
+            net.train_step(blocks[k], yd[k * 128:k * 128 + B], B)
+        states.append(([L.export_csr() for L in net.layers], net.loss_sum.item()))
+        net.close()
+    assert states[0][1] == states[1][1]
+    for la, lb in zip(states[0][0], states[1][0]):
+        for u, v in zip(la, lb):
+            assert np.array_equal(u.view(np.uint32) if u.dtype == np.float32 else u,
+                                  v.view(np.uint32) if v.dtype == np.float32 else v)
