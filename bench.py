@@ -22,9 +22,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(kernel, spec, B, has_csc):
-    """Compulsory HBM bytes of one launch (every operand once) and the no-reuse gather model (every
-    stored connection fetches its own 4*B-byte operand row)."""
+def byte_counts(kernel, spec, B, has_csc):
+    """(compulsory_bytes, gather_model_bytes) of one launch.  compulsory: every operand moved once.  gather
+    model: every stored connection fetches its own 4*B-byte operand row (no reuse of gathered rows), which is
+    what an Erdos-Renyi pattern of density 2e-5 leaves a kernel to work with."""
     nnz, n_in, n_out = spec.nnz, spec.n_in, spec.n_out
     row = 4 * B
     if kernel == "forward_spmm":
@@ -43,6 +44,13 @@ def algorithmic_bytes(kernel, spec, B, has_csc):
         b = (28 if has_csc else 20) * nnz + 20 * n_out
         return b, b
     return 0, 0
+
+
+def evolve_bytes(spec, has_csc):
+    """One prune / regrow cycle of a layer: one read of |w| for the threshold (4), compaction of column, weight and
+    velocity (12 read + 12 written, survivors and new connections together), and the rebuild of the transposed
+    view (16: row index, position, weight and velocity in the other order) per stored connection."""
+    return (44 if has_csc else 28) * spec.nnz
 
 
 def run_small(name, torch, np, binding, wl, dev, with_cpu):
@@ -75,11 +83,12 @@ def run_small(name, torch, np, binding, wl, dev, with_cpu):
                                    w.momentum, 0.0, w.seed, s.layer_id) for s in w.layers]
         onet = orc.OracleMLP(olayers)
         ns = min(8, nb)
+        cores = orc.set_threads(0)
         c0 = time.perf_counter()
         for k in range(ns):
             onet.train_step(host_blocks[k][:, : sizes[k]], ypad[k * B: k * B + sizes[k]])
         c1 = time.perf_counter()
-        rec["cpu_baseline"] = dict(value=sum(sizes[:ns]) / (c1 - c0), unit="samples/s", cores=1, kind="oracle",
+        rec["cpu_baseline"] = dict(value=sum(sizes[:ns]) / (c1 - c0), unit="samples/s", cores=cores, kind="oracle",
                                    sample=f"first {ns} training steps")
     return rec
 
@@ -91,8 +100,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="set_mlp_1m")
     ap.add_argument("--profile-steps", type=int, default=8)
-    ap.add_argument("--cpu-samples", type=int, default=32)
+    ap.add_argument("--cpu-samples", type=int, default=16, help="samples of the single-thread oracle timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the single-layer sweep points")
     ap.add_argument("--extra-workloads", default="set_mlp_madelon,set_mlp_fmnist,set_mlp_cifar",
                     help="comma list of further workloads timed for one epoch each and reported under `other_workloads`")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -166,13 +176,18 @@ def main():
     elapsed = t1 - t0
     value = samples / elapsed
 
-    # ---- evolution alone (one generation, all layers)
+    # ---- evolution alone (one generation, all layers): time, bytes of the per-connection count above, fraction
     torch.cuda.synchronize()
     te0 = time.perf_counter()
     generation[0] += 1
     net.evolve(w.zeta, generation[0])
     torch.cuda.synchronize()
     evolve_ms = (time.perf_counter() - te0) * 1e3
+    ev_bytes = sum(evolve_bytes(spec, li > 0) for li, spec in enumerate(w.layers))
+    evolve = dict(ms_all_layers=evolve_ms, connections=sum(s.nnz for s in w.layers), model_bytes=ev_bytes,
+                  model_gbs=ev_bytes / evolve_ms / 1e6, frac=ev_bytes / evolve_ms / 1e6 / HBM_PEAK_GBS,
+                  share_of_an_epoch=evolve_ms / (evolve_ms + n_blocks * elapsed / K * 1e3),
+                  note="host wall clock around sparse_layer_evolve of every layer, synchronisations included")
 
     # ---- per-kernel durations with HIP events on the launch stream
     for layer in net.layers:
@@ -184,12 +199,21 @@ def main():
     kernels = []
     for li, (layer, spec) in enumerate(zip(net.layers, w.layers)):
         for name, (n, ms) in layer.profile_end().items():
-            comp, gather = algorithmic_bytes(name, spec, B, li > 0)
+            if name == "update":
+                # one launch updates every layer (sparse_layers_update); it is timed on the first layer's handle
+                pairs = [byte_counts(name, sp_, B, k > 0) for k, sp_ in enumerate(w.layers)]
+                comp, gather = sum(p[0] for p in pairs), sum(p[1] for p in pairs)
+                label, where = "update (all layers, one launch)", "all"
+            else:
+                comp, gather = byte_counts(name, spec, B, li > 0)
+                label, where = name, li
             avg_ms = ms / n
-            kernels.append(dict(layer=li, kernel=name, launches_per_step=n / P, avg_ms=avg_ms,
-                                algorithmic_bytes=comp, gather_model_bytes=gather,
-                                achieved_gbs=comp / avg_ms / 1e6 if comp else 0.0,
-                                gather_model_gbs=gather / avg_ms / 1e6 if gather else 0.0))
+            kernels.append(dict(layer=where, kernel=label, launches_per_step=n / P, avg_ms=avg_ms,
+                                compulsory_bytes=comp, gather_model_bytes=gather,
+                                compulsory_gbs=comp / avg_ms / 1e6 if comp else 0.0,
+                                gather_model_gbs=gather / avg_ms / 1e6 if gather else 0.0,
+                                compulsory_frac=comp / avg_ms / 1e6 / HBM_PEAK_GBS if comp else 0.0,
+                                gather_model_frac=gather / avg_ms / 1e6 / HBM_PEAK_GBS if gather else 0.0))
     kernels.sort(key=lambda r: -r["avg_ms"] * r["launches_per_step"])
     dom = kernels[0]
     traffic = None
@@ -200,31 +224,49 @@ def main():
             traffic = t.get(args.workload, {}).get(f"{dom['kernel']}:L{dom['layer']}")
         except Exception:
             traffic = None
-    # `achieved` counts the per-connection algorithmic bytes (every stored connection fetches its own
-    # 4*B-byte operand row); the stricter each-operand-once count is reported beside it.
-    roofline = dict(bound="hbm", kernel=dom["kernel"], layer=dom["layer"], achieved=dom["gather_model_gbs"],
-                    peak=HBM_PEAK_GBS, unit="GB/s", frac=dom["gather_model_gbs"] / HBM_PEAK_GBS, traffic=traffic,
-                    avg_ms=dom["avg_ms"], algorithmic_bytes=dom["gather_model_bytes"],
-                    measured_gbs=(traffic / dom["avg_ms"] / 1e6) if traffic else None,
-                    compulsory_bytes=dom["algorithmic_bytes"], compulsory_achieved=dom["achieved_gbs"],
-                    compulsory_frac=dom["achieved_gbs"] / HBM_PEAK_GBS)
+    # `achieved` / `frac` count the gather-model bytes (every stored connection fetches its own 4*B-byte operand
+    # row); the each-operand-once count and its fraction stand beside them.  `traffic` is NOT measured by this
+    # run: it is the rocprofv3 reading of the same kernel and workload kept under profiles/.
+    roofline = dict(bound="hbm", bound_note="L2 <-> fabric traffic (the L2 counters cannot separate Infinity Cache hits from HBM)",
+                    kernel=dom["kernel"], layer=dom["layer"], achieved=dom["gather_model_gbs"], peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=dom["gather_model_frac"], traffic=traffic,
+                    traffic_source="profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command; not measured in this run)",
+                    avg_ms=dom["avg_ms"], gather_model_bytes=dom["gather_model_bytes"],
+                    compulsory_bytes=dom["compulsory_bytes"], compulsory_achieved=dom["compulsory_gbs"],
+                    compulsory_frac=dom["compulsory_frac"])
 
-    # ---- CPU oracle on this host, bounded sample (reported baseline, not the target)
+    # ---- CPU oracle on this host (reported baseline, not the target): one full minibatch at all host cores,
+    # and a smaller sample on one thread
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
-        ns = max(1, min(args.cpu_samples, sizes[0]))
-        xs = blocks[0][:, :ns].contiguous().cpu().numpy()
-        ys = labels[0][:ns].cpu().numpy()
         olayers = [orc.OracleLayer(s.n_in, s.n_out, s.nnz, s.act_kind, s.act_parity, w.alpha, s.init_limit, w.lr,
                                    w.momentum, 0.0, w.seed, s.layer_id) for s in w.layers]
         onet = orc.OracleMLP(olayers)
+        cores = orc.set_threads(0)
+        ns = sizes[0]
+        xs = blocks[0][:, :ns].contiguous().cpu().numpy()
+        ys = labels[0][:ns].cpu().numpy()
         c0 = time.perf_counter()
         onet.train_step(xs, ys)
         c1 = time.perf_counter()
-        cpu = dict(value=ns / (c1 - c0), unit="samples/s", cores=1, kind="oracle",
-                   sample=f"one training step (forward, loss, backward, update) on the first {ns} samples of "
-                          f"minibatch 0 at the full layer shapes; {c1 - c0:.1f} s; evolution not included")
+        n1 = max(1, min(args.cpu_samples, ns))
+        orc.set_threads(1)
+        d0 = time.perf_counter()
+        onet.train_step(np.ascontiguousarray(xs[:, :n1]), ys[:n1])
+        d1 = time.perf_counter()
+        orc.set_threads(cores)
+        e0 = time.perf_counter()
+        olayers[0].evolve(w.zeta, 1)
+        e1 = time.perf_counter()
+        cpu = dict(value=ns / (c1 - c0), unit="samples/s", cores=cores, kind="oracle",
+                   sample=f"one training step (forward, loss, backward, update) on minibatch 0 ({ns} samples) at the full "
+                          f"layer shapes, rows shared among {cores} threads: {c1 - c0:.1f} s",
+                   single_thread=dict(value=n1 / (d1 - d0), unit="samples/s", cores=1,
+                                      sample=f"the same step on the first {n1} samples, one thread: {d1 - d0:.1f} s"),
+                   evolve_first_layer_s=e1 - e0,
+                   evolve_note=f"one prune / regrow cycle of the first layer only ({w.layers[0].nnz} of "
+                               f"{sum(s.nnz for s in w.layers)} connections), one thread (sort-based)")
 
     # ---- forward only (inference): the whole network on every minibatch block, no sign masks kept
     def time_inference(model, xs, b, reps):
@@ -288,13 +330,19 @@ def main():
     for name in extra:
         others.append(run_small(name, torch, np, binding, wl, dev, not args.no_cpu_baseline))
 
+    # ---- the single-layer sweep (one 262 144 x 262 144 layer): B = 128 at every density and the weakest corners
+    sweep = None
+    if not args.no_sweep:
+        from paper_2102_01732_amd import sweep as sw
+        sweep = sw.run_points(wl.SWEEP_N, 10, [(1, 128), (4, 128), (16, 128), (64, 128), (1, 32), (1, 1024), (4, 512), (64, 32)])
+
     out = dict(metric="sparse-MLP train samples/s", value=value, unit="samples/s", n_gpus=1, steps=K,
                warmup=args.warmup, ms_per_step=elapsed / K * 1e3, higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="f32", data=data_note,
                config=dict(workload=args.workload, dims=list(w.dims), epsilon=w.epsilon, batch=B,
                            nnz=[s.nnz for s in w.layers], alpha=w.alpha, zeta=w.zeta,
                            evolutions_in_timed_region=K // n_blocks, parallelism="single GPU"),
-               roofline=roofline, cpu_baseline=cpu, evolve_ms_all_layers=evolve_ms, kernels=kernels[:12],
+               roofline=roofline, cpu_baseline=cpu, evolve=evolve, kernels=kernels[:12], sweep=sweep,
                inference=inference, importance_pruning=importance, sparse_average=average, other_workloads=others)
     print(json.dumps(out))
 
