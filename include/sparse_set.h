@@ -73,7 +73,7 @@ typedef struct sl_config {
 /* Bytes of device memory a layer with this configuration needs.  Host only, no GPU required. */
 int sparse_layer_query_sizes(const sl_config *cfg, size_t *state_bytes, size_t *scratch_bytes);
 
-/* Problem formulation + Algorithm 2 "sparse initialization": builds an Erdos-Renyi topology with
+/* Problem formulation and the initialisation step of Algorithm 2: builds an Erdos-Renyi topology with
  * exactly nnz distinct connections (generation 0 of the Philox sampler), draws the weights,
  * zeroes biases and velocities, builds CSR and (if SL_FLAG_NEED_INPUT_GRAD) the CSC view.
  * Synchronises the stream. */
@@ -86,7 +86,7 @@ int sparse_layer_init(const sl_config *cfg, void *state_dev, size_t state_bytes,
 int sparse_layer_forward(sl_layer *layer, const float *x_dev, int64_t ldx, int32_t B, float *a_dev,
                          int64_t lda, void *hip_stream);
 
-/* Forward only (the paper's test-set evaluation, its "inference bottleneck" at extreme size): the same
+/* Forward only (the paper's test-set evaluation, which its extreme-scale section names as a bottleneck): the same
  * computation as sparse_layer_forward, but nothing is saved for a backward pass and the layer's
  * training state is untouched, so it may be called between forward and backward.  Asynchronous. */
 int sparse_layer_infer(sl_layer *layer, const float *x_dev, int64_t ldx, int32_t B, float *a_dev, int64_t lda,
@@ -149,11 +149,19 @@ int sparse_layer_update(sl_layer *layer, void *hip_stream);
  * backward and update. */
 int sparse_layer_set_fused_update(sl_layer *layer, int32_t mode);
 
-/* Algorithm 2's weight pruning-regrowing cycle: removes k connections (see prune_mode), draws k
+/* The prune / regrow cycle that Algorithm 2 runs after every epoch: removes k connections (see prune_mode), draws k
  * distinct empty positions with the Philox sampler at `generation` (>= 1, < 2^32; a different
  * value per call), gives them fresh weights and zero velocity, and rebuilds CSR and the CSC
  * view.  nnz is unchanged.  k = floor(zeta*nnz + 0.5) in double.  Synchronises the stream. */
 int sparse_layer_evolve(sl_layer *layer, double zeta, uint64_t generation, void *hip_stream);
+
+/* Regrowth sampler of sparse_layer_evolve (sparse layers only).  Candidate positions t = 0, 1, 2, ... are
+ * evaluated a window [0, W) at a time; a window that accepts fewer than k positions is evaluated again twice as
+ * long.  first_window: W of the first attempt (0: chosen from the expected number of draws plus eight standard
+ * deviations); max_window: largest W tried (0: what the scratch buffer holds).  The result never depends on
+ * either; a window that cannot grow far enough makes sparse_layer_evolve return SL_ESTATE and leaves the layer
+ * exactly as it was. */
+int sparse_layer_set_sampler_window(sl_layer *layer, int64_t first_window, int64_t max_window);
 
 /* Neuron importance, eq. (4): importance[j] = sum over the stored incoming connections of neuron j of
  * |Wt[j,i]|, added in fp32 in stored order.  importance_host: host array of n_out floats.
@@ -166,8 +174,8 @@ int sparse_layer_importance(sl_layer *layer, float *importance_host);
  * NULL) receives the number of removed connections.  Synchronises the stream. */
 int sparse_layer_importance_prune(sl_layer *layer, float threshold, int64_t *removed, void *hip_stream);
 
-/* Sparse model averaging, eq. (2) and the last step of Algorithm 1 ("produce averaged model and
- * select a fraction S of weights with bigger magnitude"): dst <- (1/K) * sum of the K replicas, where
+/* Sparse model averaging: eq. (2) and the final step of Algorithm 1 (magnitude re-pruning of the averaged
+ * model back to the sparsity level S): dst <- (1/K) * sum of the K replicas, where
  * a connection that a replica does not have counts as zero; the union of the patterns is then
  * pruned by magnitude (ordering key as in sparse_layer_evolve) back to dst's current number of
  * connections.  Each value is the fp32 sum in replica order divided by K.  Biases are averaged the
@@ -197,7 +205,8 @@ int sparse_layer_retain_valid_updates(sl_layer *layer, const int32_t *old_rowptr
 /* Softmax + cross-entropy over C output neurons (the loss is unnamed in the paper).
  * z_dev [C][ldz], y_dev int32[B] (device) -> dz_dev [C][lddz] = (softmax(z) - onehot(y)) / B and
  * *loss_sum_dev += sum_b -log softmax(z)[y_b] (device float; the caller zeroes and averages it;
- * may be NULL).  C <= 1024.  Asynchronous. */
+ * may be NULL).  C <= 1024.  A label outside [0, C) means "no target": that sample adds nothing to the loss and
+ * its dz is softmax(z) / B; the label is never used as an index.  Asynchronous. */
 int sparse_loss_softmax_ce(const float *z_dev, int64_t ldz, const int32_t *y_dev, int32_t B, int32_t C,
                            float *dz_dev, int64_t lddz, float *loss_sum_dev, void *hip_stream);
 

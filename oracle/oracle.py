@@ -46,8 +46,9 @@ def build(force: bool = False) -> str:
 def lib():
     global _lib
     if _lib is None:
-        build()
-        L = ctypes.CDLL(_LIB)
+        # ORACLE_LIB: another build of the same source (the sanitizer run of the pins uses it)
+        path = os.environ.get("ORACLE_LIB") or build()
+        L = ctypes.CDLL(path)
         c = ctypes
         L.or_set_threads.argtypes = [c.c_int]
         L.or_set_threads.restype = c.c_int

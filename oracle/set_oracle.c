@@ -23,7 +23,7 @@
  *   or_weight_value       value of a freshly created connection (paper silent: uniform in
  *                         (-limit, limit), the same law at initialisation and at regrowth).
  *   or_sample_positions   k distinct empty positions, uniformly at random (Erdos-Renyi graph
- *                         with a fixed number of edges; Algorithm 2 "add randomly new weights").
+ *                         with a fixed number of edges; Algorithm 2, regrowth step).
  *   or_forward            z = Wt x + b followed by All-ReLU, eq. (3).
  *   or_backward           backpropagation through one layer: delta through eq. (3)'s
  *                         derivative, weight gradient on existing connections only
@@ -417,7 +417,7 @@ int64_t or_prune_select(int64_t nnz, const float *val, const uint64_t *flat, dou
 /* have diverged; a connection absent from a replica counts as 0.  Input: the T stored entries of   */
 /* all replicas sorted by flat position, entries of equal position in replica order.  Each run of   */
 /* equal positions is added in fp32 in that order and divided by K.  Returns the size of the union. */
-/* The paper then keeps the connections "with bigger magnitude" so that the sparsity level is       */
+/* Algorithm 1's final step then keeps the largest magnitudes so that the sparsity level is        */
 /* restored: or_keep_largest marks for removal everything but the n_keep largest (ordering key as   */
 /* in or_prune_select: smaller (|w| bits, flat position) goes first).                               */
 /* ------------------------------------------------------------------------------------------ */

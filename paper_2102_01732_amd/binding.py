@@ -29,7 +29,7 @@ EXPORTS = [
     "sparse_layer_infer", "sparse_layers_average_query", "sparse_layers_average",
     "sparse_loss_softmax_ce_into", "sparse_layers_update", "sparse_layer_set_dropout",
     "sparse_layer_retain_valid_updates", "sparse_layer_infer_static",
-    "sparse_layer_set_fused_update",
+    "sparse_layer_set_fused_update", "sparse_layer_set_sampler_window",
 ]
 N_KERNEL_IDS = 7
 
@@ -65,6 +65,7 @@ def lib():
         L.sparse_layer_backward.argtypes = [vp, f32p, i64, f32p, i64, i32, f32p, i64, vp]
         L.sparse_layer_update.argtypes = [vp, vp]
         L.sparse_layer_set_fused_update.argtypes = [vp, i32]
+        L.sparse_layer_set_sampler_window.argtypes = [vp, i64, i64]
         L.sparse_layer_evolve.argtypes = [vp, C.c_double, C.c_uint64, vp]
         L.sparse_layer_destroy.argtypes = [vp]
         L.sparse_loss_softmax_ce.argtypes = [f32p, i64, i32p, i32, i32, f32p, i64, f32p, vp]
@@ -182,6 +183,10 @@ class SparseLayer:
     def evolve(self, zeta: float, generation: int):
         self._check(lib().sparse_layer_evolve(self.handle, float(zeta), int(generation), _stream()),
                     "sparse_layer_evolve")
+
+    def set_sampler_window(self, first_window: int = 0, max_window: int = 0):
+        self._check(lib().sparse_layer_set_sampler_window(self.handle, int(first_window), int(max_window)),
+                    "sparse_layer_set_sampler_window")
 
     def retain_valid_updates(self, old_rowptr: torch.Tensor, old_colidx: torch.Tensor, old_grad: torch.Tensor,
                              old_grad_bias: torch.Tensor):

@@ -396,6 +396,15 @@ int sparse_layer_evolve(sl_layer *L, double zeta, uint64_t generation, void *hip
     return SL_OK;
 }
 
+int sparse_layer_set_sampler_window(sl_layer *L, int64_t first_window, int64_t max_window)
+{
+    if (!L) return SL_EINVAL;
+    if (first_window < 0 || max_window < 0) return set_err(L, SL_EINVAL, "sampler window must not be negative");
+    L->sampler_first = first_window;
+    L->sampler_max = max_window;
+    return SL_OK;
+}
+
 int sparse_layer_retain_valid_updates(sl_layer *L, const int32_t *old_rowptr_dev, const int32_t *old_colidx_dev,
                                       const float *old_grad_dev, int64_t old_nnz, const float *old_grad_bias_dev,
                                       void *hip_stream)

@@ -100,6 +100,7 @@ struct sl_layer {
     // pending backward pass (phase 2).
     int fuse_mode = 0;
     bool weights_updated = false, grad_stored = true;
+    int64_t sampler_first = 0, sampler_max = 0;   // window of the position sampler (0: automatic / the scratch capacity)
     int phase = 0;     // 0 idle, 1 forward done, 2 backward done
     int last_B = 0;
     hipStream_t last_stream = nullptr;

@@ -679,9 +679,12 @@ static int sample_positions(sl_layer *L, long k, long n_occ, uint32_t generation
         SL_HIP(L, hipGetLastError());
         return SL_OK;
     }
-    long W = sampler_window((double)M, (double)n_occ, (double)k);
-    for (int attempt = 0; attempt < 2; ++attempt) {
-        if (W > L->cp.w_cap) W = L->cp.w_cap;
+    // Acceptance of candidate t depends only on the candidates before it, so a window [0, W) that yields fewer than
+    // k accepted positions is simply evaluated again twice as long, until k are accepted or the capacity is reached.
+    const long cap = (L->sampler_max > 0 && L->sampler_max < L->cp.w_cap) ? (long)L->sampler_max : (long)L->cp.w_cap;
+    long W = L->sampler_first > 0 ? (long)L->sampler_first : sampler_window((double)M, (double)n_occ, (double)k);
+    for (;;) {
+        if (W > cap) W = cap;
         hipLaunchKernelGGL(cand_kernel, dim3(nblk(W)), dim3(TB), 0, s, W, r, n_in, n_out, kA, vA);
         SL_HIP(L, sort_pairs<uint64_t>(temp, L->cp.temp_bytes, kA, kB, vA, vB, (size_t)W, bit_length(M - 1), &ks, &vs, s));
         hipLaunchKernelGGL(cand_ok_kernel, dim3(nblk(W + 1)), dim3(TB), 0, s, W, ks, vs, rowptr_s, s_col, n_in, f0, f1);
@@ -696,7 +699,7 @@ static int sample_positions(sl_layer *L, long k, long n_occ, uint32_t generation
             SL_HIP(L, hipGetLastError());
             return SL_OK;
         }
-        if (W == L->cp.w_cap) break;
+        if (W >= cap) break;
         W *= 2;
     }
     return set_err(L, SL_ESTATE, "position sampler: window exhausted before %ld positions were accepted", k);

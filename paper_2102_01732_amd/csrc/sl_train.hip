@@ -778,12 +778,13 @@ __global__ __launch_bounds__(BLOCK) void softmax_ce_kernel(const float *z, long 
         float s = 0.f;
         for (int c = 0; c < C; ++c) s += expf(z[c * ldz + b] - m);
         const int yb = y[b];
+        const bool labelled = yb >= 0 && yb < C;   // a label outside [0, C) is "no target": never used as an index
         const float inv = 1.f / s;
         for (int c = 0; c < C; ++c) {
             const float p = expf(z[c * ldz + b] - m) * inv;
             dz[c * lddz + b] = (p - (c == yb ? 1.f : 0.f)) * invB;
         }
-        loss += logf(s) - (z[(long)yb * ldz + b] - m);
+        if (labelled) loss += logf(s) - (z[(long)yb * ldz + b] - m);
     }
     red[threadIdx.x] = loss;
     __syncthreads();

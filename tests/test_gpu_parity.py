@@ -1091,3 +1091,59 @@ def test_training_step_with_and_without_fused_update(gpu):
         for u, v in zip(la, lb):
             assert np.array_equal(u.view(np.uint32) if u.dtype == np.float32 else u,
                                   v.view(np.uint32) if v.dtype == np.float32 else v)
+
+
+# ------------------------------------------------------------------------------------------ sampler window
+@pytest.mark.parametrize("n_in,n_out,nnz", [(500, 400, 9000), (100000, 70000, 1700000)])
+def test_sampler_window_growth_and_failure(gpu, oracle, n_in, n_out, nnz):
+    """A first window far too short for the k positions wanted is doubled until it suffices, and the result is
+    still the oracle's sequential definition bit for bit; a window that is not allowed to grow far enough makes
+    the call fail and leaves the layer exactly as it was."""
+    G, O = make_pair(gpu, oracle, n_in, n_out, nnz, seed=61)
+    rng = np.random.default_rng(nnz)
+    rowptr, colidx, val, vel, bias, bias_vel = G.export_csr()
+    val = (rng.standard_normal(nnz) * 0.1).astype(np.float32)
+    vel = (rng.standard_normal(nnz) * 0.01).astype(np.float32)
+    G.import_csr(rowptr, colidx, val, vel, bias, bias_vel)
+    O.set_state(rowptr, colidx, val, vel, bias, bias_vel)
+    before = G.export_csr()
+    G.set_sampler_window(16, 64)                              # k is in the thousands: 64 candidates can never do
+    with pytest.raises(gpu.SparseSetError) as e:
+        G.evolve(0.3, 1)
+    assert e.value.code == gpu.SL_ESTATE and "sampler" in str(e.value)
+    after = G.export_csr()
+    assert all(np.array_equal(a.view(np.uint32) if a.dtype == np.float32 else a,
+                              b.view(np.uint32) if b.dtype == np.float32 else b) for a, b in zip(before, after))
+    # the layer still works: same forward result as before the failed call would have given, then a good evolution
+    G.set_sampler_window(16, 0)                               # sixteen candidates first, then doubling
+    O.evolve(0.3, 1)
+    G.evolve(0.3, 1)
+    assert_same_topology(G, O)
+    G.set_sampler_window(0, 0)
+    O.evolve(0.3, 2)
+    G.evolve(0.3, 2)
+    assert_same_topology(G, O)
+    G.close()
+
+
+def test_softmax_cross_entropy_label_out_of_range(gpu):
+    """A label outside [0, C) (padding, an uninitialised buffer) is never used as an index: the sample adds nothing
+    to the loss and its gradient is softmax(z) / B; the labelled samples are untouched by it."""
+    import scipy.special
+    import torch
+    rng = np.random.default_rng(4)
+    C, B = 10, 96
+    z = (rng.standard_normal((C, B)) * 3).astype(np.float32)
+    y = rng.integers(0, C, size=B).astype(np.int32)
+    bad = np.array([3, 17, 40, 95])
+    y[bad] = [-1, C, 2 ** 31 - 1, -2 ** 31]
+    zd = dev(torch, z)
+    dzd = torch.zeros((C, B), device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    gpu.softmax_ce(zd, dev(torch, y), B, C, dzd, loss)
+    logp = scipy.special.log_softmax(z.astype(np.float64), axis=0)
+    ref = np.exp(logp)
+    good = np.setdiff1d(np.arange(B), bad)
+    ref[y[good], good] -= 1
+    close(dzd.cpu().numpy(), ref / B, 1e-5, "dz")
+    assert abs(loss.item() - (-logp[y[good], good].sum())) <= 1e-4 * abs(logp[y[good], good].sum())

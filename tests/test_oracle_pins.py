@@ -612,3 +612,29 @@ def test_rounding_band_covers_an_fp32_evaluation(oracle):
         assert np.all(np.abs(a_ref) <= mag)
         assert np.all(np.abs(a32.astype(np.float64) - a_ref) <= err)
         assert np.all(err <= 1e-4 * mag) and err.max() > 0
+
+
+def test_pins_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The oracle's C file rebuilt with -fsanitize=address,undefined, and every pin above re-run through that build
+    in a child process: an out-of-bounds access, a signed overflow or a misaligned read in the checker itself
+    would fail here even where it happens not to change a result."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    so = str(tmp_path / "liboracle_san.so")
+    subprocess.check_call(["gcc", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                           "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                           os.path.join(root, "oracle", "set_oracle.c"), "-o", so, "-lm"])
+    asan = subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
+    if not os.path.isabs(asan) or not os.path.exists(asan):
+        pytest.skip("no libasan runtime beside gcc")
+    env = dict(os.environ)
+    env["ORACLE_LIB"] = so
+    env["LD_PRELOAD"] = " ".join(x for x in (asan, env.get("LD_PRELOAD", "")) if x)     # the runtime of an instrumented .so
+    env["ASAN_OPTIONS"] = "detect_leaks=0:verify_asan_link_order=0:abort_on_error=1"
+    env["UBSAN_OPTIONS"] = "halt_on_error=1:print_stacktrace=1"
+    env["OMP_NUM_THREADS"] = "2"
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.abspath(__file__), "-x", "-q", "-s", "-p", "no:cacheprovider",
+                        "-k", "not sanitizers"], cwd=root, env=env, capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-3000:]
+    assert "passed" in r.stdout
