@@ -105,6 +105,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the single-layer sweep points")
     ap.add_argument("--extra-workloads", default="set_mlp_madelon,set_mlp_fmnist,set_mlp_cifar",
                     help="comma list of further workloads timed for one epoch each and reported under `other_workloads`")
+    ap.add_argument("--evolve-only", type=int, default=0, metavar="N",
+                    help="build the network, run N prune/regrow cycles of every layer, print their times and exit "
+                         "(the command behind the per-kernel evolve profile)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -124,6 +127,18 @@ def main():
     K = args.steps if args.steps is not None else w.steps_per_epoch
     n_blocks = w.steps_per_epoch
     n_in = w.dims[0]
+
+    if args.evolve_only > 0:
+        net = binding.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=B)
+        times = []
+        for g in range(args.evolve_only):
+            torch.cuda.synchronize()
+            q0 = time.perf_counter()
+            net.evolve(w.zeta, g + 1)
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - q0) * 1e3)
+        print(json.dumps(dict(workload=args.workload, evolve_ms_all_layers=times, connections=sum(s.nnz for s in w.layers))))
+        return
 
     # ---- synthetic data, resident in HBM, feature-major minibatch blocks [n_blocks][n_in][B]
     if w.n_samples * n_in > 2 ** 28:

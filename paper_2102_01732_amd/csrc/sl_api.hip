@@ -100,6 +100,7 @@ int plan_state(const sl_config &c, int64_t nnz, StatePlan *sp)
         sp->b_v2row = take(cur, 4 * (size_t)sp->nv_cap_b);
         sp->b_rvptr = take(cur, 4 * (ni + 1));
     }
+    sp->rowid = take(cur, 4 * n);
     sp->sel = take(cur, 2 * sizeof(SelState));
     sp->total = cur;
     return SL_OK;
@@ -146,6 +147,8 @@ int plan_scratch(const sl_config &c, int64_t nnz, ScratchPlan *cp)
     cp->temp_bytes = ((size_t)32 << 20) + 2 * (w > n ? w : n);
     cp->temp = take(cur, cp->temp_bytes);
     cp->small = take(cur, 1024);
+    cp->s_row = take(cur, 4 * n);
+    cp->packed = take(cur, csc ? 16 * n : 0);   // (row, weight, velocity) per CSR slot while the transposed view is rebuilt
     cp->total = cur > train_end ? cur : train_end;
     return SL_OK;
 }
@@ -230,6 +233,7 @@ int sparse_layer_init(const sl_config *cfg, void *state_dev, size_t state_bytes,
     L->mask = (uint8_t *)(b + sp.mask); L->dz = (float *)(b + sp.dz);
     L->fwd.vptr_store = (int *)(b + sp.f_vptr); L->fwd.v2row_store = (int *)(b + sp.f_v2row);
     L->fwd.rvptr_store = (int *)(b + sp.f_rvptr); L->fwd.nv_cap = sp.nv_cap_f;
+    L->rowid = (int *)(b + sp.rowid);
     L->sel = (SelState *)(b + sp.sel);
     hipStream_t s = (hipStream_t)hip_stream;
     L->last_stream = s;

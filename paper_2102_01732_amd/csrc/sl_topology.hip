@@ -4,6 +4,7 @@
 // backward pass, virtual-row tables).  Device-wide scans and radix sorts come from rocPRIM; every
 // other step is a kernel of this file.  All steps are deterministic: the resulting CSR depends
 // only on (pattern, weights, seed, layer_id, generation).
+#include <climits>
 #include <cstring>
 
 #include <rocprim/rocprim.hpp>
@@ -229,7 +230,7 @@ __global__ void keep_flag_kernel(const float *val, long n, int mode, const SelSt
 }
 
 __global__ void compact_kernel(long n, const uint32_t *keep, const uint32_t *kscan, const int *col, const float *val,
-                               const float *vel, int *s_col, float *s_val, float *s_vel)
+                               const float *vel, const int *rowid, int *s_col, float *s_val, float *s_vel, int *s_row)
 {
     const long p = (long)blockIdx.x * TB + threadIdx.x;
     if (p >= n || !keep[p]) return;
@@ -237,6 +238,7 @@ __global__ void compact_kernel(long n, const uint32_t *keep, const uint32_t *ksc
     s_col[d] = col[p];
     s_val[d] = val[p];
     s_vel[d] = vel[p];
+    if (rowid) s_row[d] = rowid[p];
 }
 
 __global__ void survivor_rowptr_kernel(int n_rows, const int *rowptr, const uint32_t *kscan, int *rowptr_s)
@@ -288,13 +290,25 @@ __global__ void cand_ok_kernel(long W, const uint64_t *key, const uint32_t *pay,
     ok_by_t[pay[x]] = ok;
 }
 
-// in sorted order: selected = ok and fewer than k accepted candidates precede it in t order
-__global__ void cand_select_kernel(long W, const uint32_t *pay, const uint32_t *rank_by_t, uint32_t k,
-                                   uint32_t *ok_sorted)
+// The number of accepted candidates before candidate t never decreases with t, so "fewer than k accepted candidates
+// precede it" holds exactly for t < T, T = the first t whose count reaches k: one search, then a comparison per
+// candidate instead of a gather per candidate.
+__global__ void cand_limit_kernel(long W, const uint32_t *rank_by_t, uint32_t k, uint32_t *limit)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    long lo = 0, hi = W;                       // rank_by_t has W + 1 entries and rank_by_t[W] >= k
+    while (lo < hi) {
+        const long mid = lo + ((hi - lo) >> 1);
+        if (rank_by_t[mid] < k) lo = mid + 1; else hi = mid;
+    }
+    *limit = (uint32_t)lo;
+}
+// in sorted order: selected = ok and candidate index below the limit
+__global__ void cand_select_kernel(long W, const uint32_t *pay, const uint32_t *limit, uint32_t *ok_sorted)
 {
     const long x = (long)blockIdx.x * TB + threadIdx.x;
     if (x >= W) return;
-    ok_sorted[x] = (ok_sorted[x] && rank_by_t[pay[x]] < k) ? 1u : 0u;
+    ok_sorted[x] = (ok_sorted[x] && pay[x] < *limit) ? 1u : 0u;
 }
 
 __global__ void gather_selected_kernel(long W, const uint32_t *sel, const uint32_t *sscan, const uint64_t *key,
@@ -376,16 +390,88 @@ __global__ void merge_new_kernel(long k, uint32_t n_in, const int *rowptr_s, con
     vel[d] = 0.f;
 }
 
+// Matrices with many short rows (every Erdos-Renyi layer) keep the row of every CSR slot (rowid), so a survivor
+// finds its new slot with a short scan over its own row's new connections instead of two binary searches over
+// whole arrays.  The merge also leaves (row, weight, velocity) of every CSR slot packed in 16 bytes for the
+// rebuild of the transposed view, which then needs one 16-byte gather per connection instead of three 4-byte
+// gathers from three arrays.
+struct __align__(16) RowValVel { int row; float val; float vel; int pad; };
+
+__global__ void merge_survivor_rows_kernel(long ns, uint32_t n_in, const int *rowptr_s, const int *s_row, const int *s_col,
+                                           const float *s_val, const float *s_vel, const uint64_t *new_p, const int *rowptr,
+                                           int *col, float *val, float *vel, int *rowid, RowValVel *packed)
+{
+    const long sp = (long)blockIdx.x * TB + threadIdx.x;
+    if (sp >= ns) return;
+    const int j = s_row[sp], i = s_col[sp];
+    const int s0 = rowptr_s[j], d0 = rowptr[j];
+    const long t0 = (long)d0 - s0;                                             // new connections in the rows before row j
+    const int cnt = (rowptr[j + 1] - d0) - (rowptr_s[j + 1] - s0);             // new connections of row j
+    const uint64_t me = (uint64_t)j * n_in + (uint64_t)i;
+    int r = 0;                                                                 // those of them left of this survivor
+    while (r < cnt && new_p[t0 + r] < me) ++r;
+    const long d = (long)d0 + (sp - s0) + r;
+    const float w = s_val[sp], v = s_vel[sp];
+    col[d] = i; val[d] = w; vel[d] = v;
+    rowid[d] = j;
+    if (packed) packed[d] = RowValVel{j, w, v, 0};
+}
+// the new connections of such a matrix: as merge_new_kernel, and the row id / packed copy as above
+__global__ void merge_new_rows_kernel(long k, uint32_t n_in, const int *rowptr_s, const int *s_col, const uint64_t *new_p,
+                                      Rng r, float limit, int *col, float *val, float *vel, int *rowid, RowValVel *packed)
+{
+    const long t = (long)blockIdx.x * TB + threadIdx.x;
+    if (t >= k) return;
+    const uint64_t p = new_p[t];
+    const int j = (int)(p / n_in), i = (int)(p % n_in);
+    const long d = t + lower_bound_i32(s_col, rowptr_s[j], rowptr_s[j + 1], i);
+    const float w = fresh_weight(r, p, limit);
+    col[d] = i; val[d] = w; vel[d] = 0.f;
+    rowid[d] = j;
+    if (packed) packed[d] = RowValVel{j, w, 0.f, 0};
+}
+__global__ void pack_rows_kernel(int n_rows, const int *ptr, const float *val, const float *vel, int *rowid, RowValVel *packed)
+{
+    const int r = blockIdx.x * TB + threadIdx.x;
+    if (r >= n_rows) return;
+    for (int p = ptr[r]; p < ptr[r + 1]; ++p) {
+        rowid[p] = r;
+        if (packed) packed[p] = RowValVel{r, val[p], vel[p], 0};
+    }
+}
+__global__ void csc_fill_packed_kernel(long n, const uint32_t *pos_sorted, const RowValVel *packed, int *rowidx, int *csr_pos,
+                                       float *valT, float *velT)
+{
+    const long q = (long)blockIdx.x * TB + threadIdx.x;
+    if (q >= n) return;
+    const int p = (int)pos_sorted[q];
+    const RowValVel e = packed[p];
+    csr_pos[q] = p;
+    rowidx[q] = e.row;
+    valT[q] = e.val;
+    velT[q] = e.vel;
+}
+__global__ void copy_u32_kernel(const uint32_t *src, uint32_t *dst)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *dst = *src;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Derived structures
 // ------------------------------------------------------------------------------------------------
 __global__ void max_len_kernel(int n_rows, const int *ptr, int *out)
 {
+    __shared__ int part[TB / 64];
     int m = 0;
     for (long r = (long)blockIdx.x * TB + threadIdx.x; r < n_rows; r += (long)gridDim.x * TB)
         m = max(m, ptr[r + 1] - ptr[r]);
     for (int s = 32; s >= 1; s >>= 1) m = max(m, __shfl_xor(m, s));
-    if ((threadIdx.x & 63) == 0) atomicMax(out, m);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {                    // one atomic per block, on a few hundred blocks
+        for (int w = 1; w < TB / 64; ++w) m = max(m, part[w]);
+        atomicMax(out, m);
+    }
 }
 __global__ void vcount_kernel(int n_rows, const int *ptr, int seg, uint32_t *cnt)
 {
@@ -407,13 +493,6 @@ __global__ void vfill_kernel(int n_rows, const int *ptr, int seg, const int *rvp
     const int r = row_of(rvptr, n_rows, v);
     vptr[v] = ptr[r] + (v - rvptr[r]) * seg;
     v2row[v] = r;
-}
-// one thread per row writes the row index of each of its entries (rows are short where this is used)
-__global__ void expand_rows_kernel(int n_rows, const int *ptr, int *rowid)
-{
-    const int r = blockIdx.x * TB + threadIdx.x;
-    if (r >= n_rows) return;
-    for (int p = ptr[r]; p < ptr[r + 1]; ++p) rowid[p] = r;
 }
 __global__ void iota_copy_kernel(long n, const int *col, uint32_t *key, uint32_t *pay)
 {
@@ -572,14 +651,23 @@ static Rng make_rng(const sl_layer *L, uint32_t generation)
     return r;
 }
 
-static int build_vrows(sl_layer *L, SegMat &m, int nnz, hipStream_t s)
+// slots of the `small` scratch region (one read-back fetches what several steps left there)
+enum { SMALL_MAXLEN_F = 0, SMALL_MAXLEN_B = 1, SMALL_KEPT = 2, SMALL_ACCEPTED = 3, SMALL_CLASS = 4, SMALL_LIMIT = 5 };
+
+static bool short_rows(const sl_layer *L)   // many rows, none of them expected to be long: the per-row kernels apply
+{
+    return L->cfg.n_out >= 8192 && L->nnz <= 512 * L->cfg.n_out;
+}
+
+static void launch_max_len(sl_layer *L, const SegMat &m, int slot, hipStream_t s)
 {
     int *small = at<int>(L, L->cp.small);
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(TB), 0, s, 1L, small, 0);
-    hipLaunchKernelGGL(max_len_kernel, dim3(std::min(1024u, nblk(m.n_rows))), dim3(TB), 0, s, m.n_rows, m.ptr, small);
-    int maxlen = 0;
-    int rc = read_back(L, &maxlen, small, sizeof(int), s);
-    if (rc) return rc;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(TB), 0, s, 1L, small + slot, 0);
+    hipLaunchKernelGGL(max_len_kernel, dim3(std::min(256u, nblk(m.n_rows))), dim3(TB), 0, s, m.n_rows, m.ptr, small + slot);
+}
+
+static int finish_vrows(sl_layer *L, SegMat &m, int nnz, int maxlen, hipStream_t s)
+{
     m.seg = choose_seg(m.n_rows, nnz);
     if (maxlen <= m.seg) {
         m.split = 0; m.vptr = m.ptr; m.v2row = nullptr; m.rvptr = nullptr; m.nv = m.n_rows;
@@ -590,7 +678,7 @@ static int build_vrows(sl_layer *L, SegMat &m, int nnz, hipStream_t s)
     SL_HIP(L, scan_excl<uint32_t>(at<char>(L, L->cp.temp), L->cp.temp_bytes, cnt, (uint32_t *)m.rvptr_store,
                                   (size_t)m.n_rows + 1, s));
     int nv = 0;
-    rc = read_back(L, &nv, m.rvptr_store + m.n_rows, sizeof(int), s);
+    int rc = read_back(L, &nv, m.rvptr_store + m.n_rows, sizeof(int), s);
     if (rc) return rc;
     if (nv > m.nv_cap) return set_err(L, SL_ENOMEM, "virtual rows %d exceed capacity %d", nv, m.nv_cap);
     hipLaunchKernelGGL(vfill_kernel, dim3(nblk(nv + 1)), dim3(TB), 0, s, m.n_rows, m.ptr, m.seg, m.rvptr_store,
@@ -600,34 +688,48 @@ static int build_vrows(sl_layer *L, SegMat &m, int nnz, hipStream_t s)
     return SL_OK;
 }
 
-int topo_finalize(sl_layer *L, hipStream_t s)
+// packed_ready: the caller has already left (row, weight, velocity) of every CSR slot in the `packed` scratch region
+int topo_finalize(sl_layer *L, hipStream_t s, bool packed_ready)
 {
     const int n = (int)L->nnz, n_in = (int)L->cfg.n_in, n_out = (int)L->cfg.n_out;
     L->fwd.n_rows = n_out; L->fwd.ptr = L->rowptr; L->fwd.idx = L->colidx;
-    int rc = build_vrows(L, L->fwd, n, s);
-    if (rc) return rc;
-    if (!L->has_csc) return SL_OK;
-    // CSC view: stable sort of (column, CSR position) keeps rows ascending inside a column
-    uint32_t *kA = at<uint32_t>(L, L->cp.keyA), *kB = at<uint32_t>(L, L->cp.keyB);
-    uint32_t *vA = at<uint32_t>(L, L->cp.payA), *vB = at<uint32_t>(L, L->cp.payB);
-    uint32_t *ks = kA, *vs = vA;
-    if (n > 0) {
-        hipLaunchKernelGGL(iota_copy_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, L->colidx, kA, vA);
-        SL_HIP(L, sort_pairs<uint32_t>(at<char>(L, L->cp.temp), L->cp.temp_bytes, kA, kB, vA, vB, (size_t)n,
-                                       bit_length((uint64_t)n_in - 1), &ks, &vs, s));
-        // row index of every CSR slot: expanded once per row when rows are short, else found by search
-        int *rowid = nullptr;
-        if (!L->fwd.split) {
-            rowid = (int *)(vs == vA ? vB : vA);   // the payload buffer the sort left free
-            hipLaunchKernelGGL(expand_rows_kernel, dim3(nblk(n_out)), dim3(TB), 0, s, n_out, L->rowptr, rowid);
+    launch_max_len(L, L->fwd, SMALL_MAXLEN_F, s);
+    if (L->has_csc) {
+        // CSC view: stable sort of (column, CSR position) keeps rows ascending inside a column
+        uint32_t *kA = at<uint32_t>(L, L->cp.keyA), *kB = at<uint32_t>(L, L->cp.keyB);
+        uint32_t *vA = at<uint32_t>(L, L->cp.payA), *vB = at<uint32_t>(L, L->cp.payB);
+        uint32_t *ks = kA, *vs = vA;
+        if (n > 0) {
+            hipLaunchKernelGGL(iota_copy_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, L->colidx, kA, vA);
+            SL_HIP(L, sort_pairs<uint32_t>(at<char>(L, L->cp.temp), L->cp.temp_bytes, kA, kB, vA, vB, (size_t)n,
+                                           bit_length((uint64_t)n_in - 1), &ks, &vs, s));
+            if (short_rows(L)) {
+                RowValVel *packed = at<RowValVel>(L, L->cp.packed);
+                if (!packed_ready)
+                    hipLaunchKernelGGL(pack_rows_kernel, dim3(nblk(n_out)), dim3(TB), 0, s, n_out, L->rowptr, L->val, L->vel,
+                                       L->rowid, packed);
+                hipLaunchKernelGGL(csc_fill_packed_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, vs, packed, L->rowidx,
+                                   L->csr_pos, L->valT, L->velT);
+            } else {
+                // few, long rows: the row of a CSR slot is found by search in the row pointers
+                hipLaunchKernelGGL(csc_fill_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, n_out, L->rowptr, (const int *)nullptr,
+                                   vs, L->val, L->vel, L->rowidx, L->csr_pos, L->valT, L->velT);
+            }
         }
-        hipLaunchKernelGGL(csc_fill_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, n_out, L->rowptr, rowid, vs, L->val,
-                           L->vel, L->rowidx, L->csr_pos, L->valT, L->velT);
+        hipLaunchKernelGGL(colptr_kernel, dim3(nblk(n_in + 1)), dim3(TB), 0, s, n_in, ks, (long)n, L->colptr);
+        L->bwd.n_rows = n_in; L->bwd.ptr = L->colptr; L->bwd.idx = L->rowidx;
+        launch_max_len(L, L->bwd, SMALL_MAXLEN_B, s);
     }
-    hipLaunchKernelGGL(colptr_kernel, dim3(nblk(n_in + 1)), dim3(TB), 0, s, n_in, ks, (long)n, L->colptr);
+    if (!L->has_csc && short_rows(L) && !packed_ready && n > 0)
+        hipLaunchKernelGGL(pack_rows_kernel, dim3(nblk(n_out)), dim3(TB), 0, s, n_out, L->rowptr, L->val, L->vel, L->rowid,
+                           (RowValVel *)nullptr);
     SL_HIP(L, hipGetLastError());
-    L->bwd.n_rows = n_in; L->bwd.ptr = L->colptr; L->bwd.idx = L->rowidx;
-    return build_vrows(L, L->bwd, n, s);
+    int maxlen[2] = {0, 0};
+    int rc = read_back(L, maxlen, at<int>(L, L->cp.small) + SMALL_MAXLEN_F, sizeof(int) * (L->has_csc ? 2 : 1), s);
+    if (rc) return rc;
+    rc = finish_vrows(L, L->fwd, n, maxlen[0], s);
+    if (rc || !L->has_csc) return rc;
+    return finish_vrows(L, L->bwd, n, maxlen[1], s);
 }
 
 int topo_sync_csr_vel(sl_layer *L, hipStream_t s)
@@ -649,7 +751,9 @@ int topo_sync_csr_grad(sl_layer *L, float *grad_csr_dev, hipStream_t s)
 
 // Draws k distinct positions that are empty w.r.t. the survivors (rowptr_s, s_col) into new_p,
 // ascending.  n_occ = number of survivors.
-static int sample_positions(sl_layer *L, long k, long n_occ, uint32_t generation, hipStream_t s)
+// expect_kept >= 0: the survivor count that the caller left in the SMALL_KEPT slot must equal it (checked at the first
+// read-back; -1: nothing to check)
+static int sample_positions(sl_layer *L, long k, long n_occ, uint32_t generation, hipStream_t s, long expect_kept)
 {
     if (k == 0) return SL_OK;
     const uint32_t n_in = (uint32_t)L->cfg.n_in, n_out = (uint32_t)L->cfg.n_out;
@@ -666,6 +770,12 @@ static int sample_positions(sl_layer *L, long k, long n_occ, uint32_t generation
     const bool dense_mode = (double)M <= 4.0 * (double)(n_occ + k);   // the definition's rule on the current nnz
     if (dense_mode && (int64_t)M > L->cp.w_cap) return set_err(L, SL_ENOMEM, "dense sampler needs %llu slots", (unsigned long long)M);
     if (dense_mode) {
+        if (expect_kept >= 0) {
+            uint32_t kept = 0;
+            int rc = read_back(L, &kept, at<uint32_t>(L, L->cp.small) + SMALL_KEPT, sizeof(uint32_t), s);
+            if (rc) return rc;
+            if ((long)kept != expect_kept) return set_err(L, SL_ESTATE, "prune kept %u entries, expected %ld", kept, expect_kept);
+        }
         const long Ml = (long)M;
         hipLaunchKernelGGL(empty_flag_kernel, dim3(nblk(Ml + 1)), dim3(TB), 0, s, Ml, rowptr_s, s_col, n_in, f0);
         SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, f0, f1, (size_t)Ml + 1, s));
@@ -689,11 +799,19 @@ static int sample_positions(sl_layer *L, long k, long n_occ, uint32_t generation
         SL_HIP(L, sort_pairs<uint64_t>(temp, L->cp.temp_bytes, kA, kB, vA, vB, (size_t)W, bit_length(M - 1), &ks, &vs, s));
         hipLaunchKernelGGL(cand_ok_kernel, dim3(nblk(W + 1)), dim3(TB), 0, s, W, ks, vs, rowptr_s, s_col, n_in, f0, f1);
         SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, f1, f2, (size_t)W + 1, s));
-        uint32_t accepted = 0;
-        int rc = read_back(L, &accepted, f2 + W, sizeof(uint32_t), s);
+        // one read-back fetches the number of accepted candidates and the survivor count that the pruning left
+        uint32_t *small = at<uint32_t>(L, L->cp.small);
+        hipLaunchKernelGGL(copy_u32_kernel, dim3(1), dim3(64), 0, s, f2 + W, small + SMALL_ACCEPTED);
+        uint32_t both[2] = {0, 0};
+        int rc = read_back(L, both, small + SMALL_KEPT, sizeof(both), s);
         if (rc) return rc;
+        if (expect_kept >= 0 && (long)both[0] != expect_kept)
+            return set_err(L, SL_ESTATE, "prune kept %u entries, expected %ld", both[0], expect_kept);
+        expect_kept = -1;
+        const uint32_t accepted = both[1];
         if ((long)accepted >= k) {
-            hipLaunchKernelGGL(cand_select_kernel, dim3(nblk(W)), dim3(TB), 0, s, W, vs, f2, (uint32_t)k, f0);
+            hipLaunchKernelGGL(cand_limit_kernel, dim3(1), dim3(64), 0, s, W, f2, (uint32_t)k, small + SMALL_LIMIT);
+            hipLaunchKernelGGL(cand_select_kernel, dim3(nblk(W)), dim3(TB), 0, s, W, vs, small + SMALL_LIMIT, f0);
             SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, f0, f3, (size_t)W + 1, s));
             hipLaunchKernelGGL(gather_selected_kernel, dim3(nblk(W)), dim3(TB), 0, s, W, f0, f3, ks, new_p);
             SL_HIP(L, hipGetLastError());
@@ -706,25 +824,38 @@ static int sample_positions(sl_layer *L, long k, long n_occ, uint32_t generation
 }
 
 // survivors (ns of them, in scratch) + k new connections at `generation` -> CSR arrays of L
-static int rebuild(sl_layer *L, long ns, long k, uint32_t generation, hipStream_t s)
+static int rebuild(sl_layer *L, long ns, long k, uint32_t generation, hipStream_t s, long expect_kept)
 {
     const int n_out = (int)L->cfg.n_out;
     const uint32_t n_in = (uint32_t)L->cfg.n_in;
-    int rc = sample_positions(L, k, ns, generation, s);
+    int rc = sample_positions(L, k, ns, generation, s, expect_kept);
     if (rc) return rc;
     const int *rowptr_s = at<int>(L, L->cp.rowptr_s), *s_col = at<int>(L, L->cp.s_col);
     const float *s_val = at<float>(L, L->cp.s_val), *s_vel = at<float>(L, L->cp.s_vel);
     const uint64_t *new_p = at<uint64_t>(L, L->cp.new_p);
     hipLaunchKernelGGL(merge_rowptr_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, n_out, n_in, rowptr_s, new_p, k,
                        L->rowptr);
-    if (ns > 0)
-        hipLaunchKernelGGL(merge_survivor_kernel, dim3(nblk(ns)), dim3(TB), 0, s, ns, n_out, n_in, rowptr_s, s_col,
-                           s_val, s_vel, new_p, k, L->colidx, L->val, L->vel);
-    if (k > 0)
-        hipLaunchKernelGGL(merge_new_kernel, dim3(nblk(k)), dim3(TB), 0, s, k, n_in, rowptr_s, s_col, new_p,
-                           make_rng(L, generation), L->cfg.init_limit, L->colidx, L->val, L->vel);
+    bool packed = false;
+    if (short_rows(L)) {
+        packed = true;      // row ids (and, with a transposed view, the packed copy) are written by the merge itself
+        RowValVel *pk = L->has_csc ? at<RowValVel>(L, L->cp.packed) : (RowValVel *)nullptr;
+        if (ns > 0)
+            hipLaunchKernelGGL(merge_survivor_rows_kernel, dim3(nblk(ns)), dim3(TB), 0, s, ns, n_in, rowptr_s,
+                               at<int>(L, L->cp.s_row), s_col, s_val, s_vel, new_p, L->rowptr, L->colidx, L->val, L->vel,
+                               L->rowid, pk);
+        if (k > 0)
+            hipLaunchKernelGGL(merge_new_rows_kernel, dim3(nblk(k)), dim3(TB), 0, s, k, n_in, rowptr_s, s_col, new_p,
+                               make_rng(L, generation), L->cfg.init_limit, L->colidx, L->val, L->vel, L->rowid, pk);
+    } else {
+        if (ns > 0)
+            hipLaunchKernelGGL(merge_survivor_kernel, dim3(nblk(ns)), dim3(TB), 0, s, ns, n_out, n_in, rowptr_s, s_col,
+                               s_val, s_vel, new_p, k, L->colidx, L->val, L->vel);
+        if (k > 0)
+            hipLaunchKernelGGL(merge_new_kernel, dim3(nblk(k)), dim3(TB), 0, s, k, n_in, rowptr_s, s_col, new_p,
+                               make_rng(L, generation), L->cfg.init_limit, L->colidx, L->val, L->vel);
+    }
     SL_HIP(L, hipGetLastError());
-    return topo_finalize(L, s);
+    return topo_finalize(L, s, packed);
 }
 
 // RetainValidUpdates (Algorithm 1): the gradient of master entry t is the old gradient of the same
@@ -784,8 +915,8 @@ int topo_importance_prune(sl_layer *L, float threshold, int64_t *removed, hipStr
     rc = read_back(L, &kept, kscan + n, sizeof(uint32_t), s);
     if (rc) return rc;
     if ((long)kept == n) return SL_OK;
-    hipLaunchKernelGGL(compact_kernel, dim3(nblk(n)), dim3(TB), 0, s, n, keep, kscan, L->colidx, L->val, L->vel, s_col,
-                       s_val, s_vel);
+    hipLaunchKernelGGL(compact_kernel, dim3(nblk(n)), dim3(TB), 0, s, n, keep, kscan, L->colidx, L->val, L->vel,
+                       (const int *)nullptr, s_col, s_val, s_vel, (int *)nullptr);
     hipLaunchKernelGGL(survivor_rowptr_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, n_out, L->rowptr, kscan, rowptr_s);
     hipLaunchKernelGGL(copy_back_kernel, dim3(nblk(kept)), dim3(TB), 0, s, (long)kept, s_col, s_val, s_vel, L->colidx,
                        L->val, L->vel);
@@ -880,7 +1011,7 @@ int topo_init(sl_layer *L, hipStream_t s)
     hipLaunchKernelGGL(fill_f32_kernel, dim3(nblk(n_out)), dim3(TB), 0, s, (long)n_out, L->grad_bias, 0.f);
     if (L->nnz > 0) hipLaunchKernelGGL(fill_f32_kernel, dim3(nblk(L->nnz)), dim3(TB), 0, s, (long)L->nnz, L->grad, 0.f);
     SL_HIP(L, hipGetLastError());
-    return rebuild(L, 0, L->nnz, 0u, s);
+    return rebuild(L, 0, L->nnz, 0u, s, -1);
 }
 
 int topo_evolve(sl_layer *L, double zeta, uint32_t generation, hipStream_t s)
@@ -893,7 +1024,7 @@ int topo_evolve(sl_layer *L, double zeta, uint32_t generation, hipStream_t s)
     // number of removals per class, floor(zeta*count + 0.5) in double
     long cnt[2] = {n, 0};
     if (mode == 1) {
-        uint32_t *small = at<uint32_t>(L, L->cp.small);
+        uint32_t *small = at<uint32_t>(L, L->cp.small) + SMALL_CLASS;
         hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(TB), 0, s, 1L, small);
         if (n > 0) hipLaunchKernelGGL(class_count_kernel, dim3(std::min(1024u, nblk(n))), dim3(TB), 0, s, L->val, n, small);
         uint32_t neg = 0;
@@ -922,14 +1053,13 @@ int topo_evolve(sl_layer *L, double zeta, uint32_t generation, hipStream_t s)
     hipLaunchKernelGGL(keep_flag_kernel, dim3(nblk(n + 1)), dim3(TB), 0, s, L->val, n, mode, L->sel, trank, keep);
     SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, keep, kscan, (size_t)n + 1, s));
     hipLaunchKernelGGL(compact_kernel, dim3(nblk(n)), dim3(TB), 0, s, n, keep, kscan, L->colidx, L->val, L->vel,
-                       at<int>(L, L->cp.s_col), at<float>(L, L->cp.s_val), at<float>(L, L->cp.s_vel));
+                       short_rows(L) ? L->rowid : (const int *)nullptr, at<int>(L, L->cp.s_col), at<float>(L, L->cp.s_val),
+                       at<float>(L, L->cp.s_vel), at<int>(L, L->cp.s_row));
     hipLaunchKernelGGL(survivor_rowptr_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, n_out, L->rowptr, kscan,
                        at<int>(L, L->cp.rowptr_s));
-    uint32_t kept = 0;
-    rc = read_back(L, &kept, kscan + n, sizeof(uint32_t), s);
-    if (rc) return rc;
-    if ((long)kept != n - k) return set_err(L, SL_ESTATE, "prune kept %u entries, expected %ld", kept, n - k);
-    return rebuild(L, n - k, k, generation, s);
+    // the survivor count is checked at the sampler's read-back
+    hipLaunchKernelGGL(copy_u32_kernel, dim3(1), dim3(64), 0, s, kscan + n, at<uint32_t>(L, L->cp.small) + SMALL_KEPT);
+    return rebuild(L, n - k, k, generation, s, n - k);
 }
 
 }  // namespace sl
