@@ -54,6 +54,14 @@
 #include <omp.h>
 #endif
 
+/* Storage type of the training step (or_all_relu, or_forward, or_backward, or_update, or_softmax_ce).  float is the
+ * paper's precision and the only build the parity tests use; -DOR_REAL=double builds the same source with double
+ * storage, which lets a finite-difference pin check the backward pass to 1e-6 instead of to what fp32 allows. */
+#ifndef OR_REAL
+#define OR_REAL float
+#endif
+typedef OR_REAL or_real;
+
 /* Number of threads for the loops described in the header (0 or less: the OpenMP default).  Returns
  * the number that will be used (1 without OpenMP). */
 int or_set_threads(int n)
@@ -229,28 +237,28 @@ int or_sample_positions(int64_t n_in, int64_t n_out, int64_t k, const uint64_t *
 /* neuron layer index l is even and +alpha when it is odd.  act_kind 0 = identity (output      */
 /* layer, excluded by the paper from eq. (3)).                                                 */
 /* ------------------------------------------------------------------------------------------ */
-static float all_relu(float z, int act_kind, int parity, float alpha)
+static or_real all_relu(or_real z, int act_kind, int parity, or_real alpha)
 {
     if (act_kind == 0 || z > 0.0f) return z;
     return parity == 0 ? (-alpha) * z : alpha * z;
 }
 
-static float all_relu_slope(float z, int act_kind, int parity, float alpha)
+static or_real all_relu_slope(or_real z, int act_kind, int parity, or_real alpha)
 {
     if (act_kind == 0 || z > 0.0f) return 1.0f;
     return parity == 0 ? -alpha : alpha;
 }
 
-void or_all_relu(const float *z, int64_t n, int act_kind, int parity, float alpha, float *a)
+void or_all_relu(const or_real *z, int64_t n, int act_kind, int parity, or_real alpha, or_real *a)
 {
     for (int64_t t = 0; t < n; ++t) a[t] = all_relu(z[t], act_kind, parity, alpha);
 }
 
 /* Forward of one layer for a minibatch of B samples:
  *   z[j][b] = bias[j] + sum_{i in Gamma_j} Wt[j,i] * x[i][b];  a[j][b] = f_l(z[j][b]). */
-void or_forward(int64_t n_out, const int32_t *rowptr, const int32_t *colidx, const float *val,
-                const float *bias, const float *x, int64_t ldx, int32_t B, int act_kind,
-                int parity, float alpha, float *z, float *a, int64_t ldo)
+void or_forward(int64_t n_out, const int32_t *rowptr, const int32_t *colidx, const or_real *val,
+                const or_real *bias, const or_real *x, int64_t ldx, int32_t B, int act_kind,
+                int parity, or_real alpha, or_real *z, or_real *a, int64_t ldo)
 {
 #pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < n_out; ++j) {
@@ -258,7 +266,7 @@ void or_forward(int64_t n_out, const int32_t *rowptr, const int32_t *colidx, con
             double acc = (double)bias[j];
             for (int32_t p = rowptr[j]; p < rowptr[j + 1]; ++p)
                 acc += (double)val[p] * (double)x[(int64_t)colidx[p] * ldx + b];
-            float zf = (float)acc;
+            or_real zf = (or_real)acc;
             z[j * ldo + b] = zf;
             a[j * ldo + b] = all_relu(zf, act_kind, parity, alpha);
         }
@@ -273,25 +281,25 @@ void or_forward(int64_t n_out, const int32_t *rowptr, const int32_t *colidx, con
  *   grad_x[i][b] = sum_{j : (j,i) stored} Wt[j,i] * dz[j][b]   (skipped when grad_x == NULL)
  * The 1/B of the minibatch mean lives in grad_a of the last layer (see or_softmax_ce). */
 int or_backward(int64_t n_in, int64_t n_out, const int32_t *rowptr, const int32_t *colidx,
-                const float *val, const float *x, int64_t ldx, const float *z,
-                const float *grad_a, int64_t ldo, int32_t B, int act_kind, int parity,
-                float alpha, float *dz, float *grad_val, float *grad_bias, float *grad_x,
+                const or_real *val, const or_real *x, int64_t ldx, const or_real *z,
+                const or_real *grad_a, int64_t ldo, int32_t B, int act_kind, int parity,
+                or_real alpha, or_real *dz, or_real *grad_val, or_real *grad_bias, or_real *grad_x,
                 int64_t ldgx)
 {
 #pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < n_out; ++j) {
         double sb = 0.0;
         for (int32_t b = 0; b < B; ++b) {
-            float d = grad_a[j * ldo + b] * all_relu_slope(z[j * ldo + b], act_kind, parity, alpha);
+            or_real d = grad_a[j * ldo + b] * all_relu_slope(z[j * ldo + b], act_kind, parity, alpha);
             dz[j * ldo + b] = d;
             sb += (double)d;
         }
-        grad_bias[j] = (float)sb;
+        grad_bias[j] = (or_real)sb;
         for (int32_t p = rowptr[j]; p < rowptr[j + 1]; ++p) {
             int64_t i = colidx[p];
             double s = 0.0;
             for (int32_t b = 0; b < B; ++b) s += (double)dz[j * ldo + b] * (double)x[i * ldx + b];
-            grad_val[p] = (float)s;
+            grad_val[p] = (or_real)s;
         }
     }
     if (grad_x) {
@@ -311,7 +319,7 @@ int or_backward(int64_t n_in, int64_t n_out, const int32_t *rowptr, const int32_
         }
 #pragma omp parallel for schedule(static)
         for (int64_t i = 0; i < n_in; ++i)
-            for (int32_t b = 0; b < B; ++b) grad_x[i * ldgx + b] = (float)acc[i * B + b];
+            for (int32_t b = 0; b < B; ++b) grad_x[i * ldgx + b] = (or_real)acc[i * B + b];
         free(acc);
     }
     return 0;
@@ -344,13 +352,13 @@ void or_dropout_apply(float *a, const uint8_t *keep, int64_t n, float scale)
 /* Momentum SGD, eq. (1): w_{t+1} = w_t + mu (w_t - w_{t-1}) - eta grad.  With vel_t = w_t -
  * w_{t-1} (vel_0 = 0) this is vel <- mu*vel - eta*(grad + lambda*w);  w <- w + vel, evaluated in
  * fp32 in exactly this order (lambda = 0 in every workload). */
-void or_update(int64_t n, float *val, float *vel, const float *grad, float lr, float momentum,
-               float weight_decay)
+void or_update(int64_t n, or_real *val, or_real *vel, const or_real *grad, or_real lr, or_real momentum,
+               or_real weight_decay)
 {
 #pragma omp parallel for schedule(static)
     for (int64_t t = 0; t < n; ++t) {
-        float g = grad[t] + weight_decay * val[t];
-        float v = momentum * vel[t] - lr * g;
+        or_real g = grad[t] + weight_decay * val[t];
+        or_real v = momentum * vel[t] - lr * g;
         vel[t] = v;
         val[t] = val[t] + v;
     }
@@ -460,8 +468,8 @@ int64_t or_keep_largest(int64_t n, const float *val, const uint64_t *flat, int64
 /* p = softmax(z) in double with the maximum subtracted; loss = -(1/B) sum_b log p[y_b];       */
 /* dz = (p - onehot(y)) / B rounded to fp32, B = the actual number of samples of this batch.   */
 /* ------------------------------------------------------------------------------------------ */
-double or_softmax_ce(const float *z, int64_t ldz, const int32_t *y, int32_t B, int32_t C,
-                     float *dz, int64_t lddz)
+double or_softmax_ce(const or_real *z, int64_t ldz, const int32_t *y, int32_t B, int32_t C,
+                     or_real *dz, int64_t lddz)
 {
     double loss = 0.0;
     for (int32_t b = 0; b < B; ++b) {
@@ -473,7 +481,7 @@ double or_softmax_ce(const float *z, int64_t ldz, const int32_t *y, int32_t B, i
         for (int32_t c = 0; c < C; ++c) {
             double p = exp((double)z[c * ldz + b] - m) / s;
             double t = (c == y[b]) ? 1.0 : 0.0;
-            dz[c * lddz + b] = (float)((p - t) / (double)B);
+            dz[c * lddz + b] = (or_real)((p - t) / (double)B);
         }
         loss -= ((double)z[(int64_t)y[b] * ldz + b] - m) - log(s);
     }

@@ -638,3 +638,88 @@ def test_pins_under_address_and_undefined_behaviour_sanitizers(tmp_path):
                         "-k", "not sanitizers"], cwd=root, env=env, capture_output=True, text=True, timeout=900)
     assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-3000:]
     assert "passed" in r.stdout
+
+
+def test_gradients_against_finite_differences_in_double_storage(oracle, tmp_path):
+    """The oracle's C file built with -DOR_REAL=double (the same source, double storage): forward, loss and backward
+    of a three-layer network through that build, against central differences of its own loss in every stored
+    weight, every bias and every input of the second layer, to 1e-6 -- a hundred times tighter than fp32 storage
+    allows, so a term that is slightly wrong (a slope, a 1/B, a transposed index) cannot hide in rounding."""
+    import ctypes as C
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    so = str(tmp_path / "liboracle_f64.so")
+    subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-DOR_REAL=double", "-fPIC", "-shared", "-std=c11",
+                           os.path.join(root, "oracle", "set_oracle.c"), "-o", so, "-lm"])
+    L = C.CDLL(so)
+    f64 = np.ctypeslib.ndpointer(dtype=np.float64, flags="C_CONTIGUOUS")
+    i32 = np.ctypeslib.ndpointer(dtype=np.int32, flags="C_CONTIGUOUS")
+    L.or_forward.argtypes = [C.c_int64, i32, i32, f64, f64, f64, C.c_int64, C.c_int32, C.c_int, C.c_int, C.c_double, f64, f64,
+                             C.c_int64]
+    L.or_forward.restype = None
+    L.or_backward.argtypes = [C.c_int64, C.c_int64, i32, i32, f64, f64, C.c_int64, f64, f64, C.c_int64, C.c_int32, C.c_int,
+                              C.c_int, C.c_double, f64, f64, f64, C.c_void_p, C.c_int64]
+    L.or_backward.restype = C.c_int
+    L.or_softmax_ce.argtypes = [f64, C.c_int64, i32, C.c_int32, C.c_int32, f64, C.c_int64]
+    L.or_softmax_ce.restype = C.c_double
+
+    dims, nnzs, B, alpha = (7, 6, 5, 3), (20, 16, 12), 4, 0.6
+    rng = np.random.default_rng(12)
+    pats = [make_layer(oracle, dims[li], dims[li + 1], nnzs[li], seed=91, layer_id=li) for li in range(3)]   # patterns only
+    val = [rng.uniform(-0.9, 0.9, n) for n in nnzs]
+    bias = [rng.standard_normal(dims[li + 1]) * 0.3 for li in range(3)]
+    x = rng.standard_normal((dims[0], B))
+    y = rng.integers(0, dims[-1], size=B).astype(np.int32)
+    kinds = [(1, 0), (1, 1), (0, 0)]            # (act_kind, parity): slopes -alpha, +alpha, identity
+
+    def forward(val, bias, x_in, first=0):
+        acts, zs = [x_in], []
+        for li in range(first, 3):
+            P = pats[li]
+            z = np.zeros((P.n_out, B))
+            a = np.zeros((P.n_out, B))
+            L.or_forward(P.n_out, P.rowptr, P.colidx, np.ascontiguousarray(val[li]), np.ascontiguousarray(bias[li]),
+                         np.ascontiguousarray(acts[-1]), B, B, kinds[li][0], kinds[li][1], alpha, z, a, B)
+            zs.append(z)
+            acts.append(a)
+        dz = np.zeros((dims[-1], B))
+        loss = L.or_softmax_ce(np.ascontiguousarray(acts[-1]), B, y, B, dims[-1], dz, B)
+        return loss, acts, zs, dz
+
+    loss, acts, zs, grad = forward(val, bias, x)
+    assert min(np.abs(z).min() for z in zs[:2]) > 1e-3                     # away from the kink of eq. (3)
+    g_val, g_bias, g_in = [None] * 3, [None] * 3, [None] * 3
+    for li in (2, 1, 0):
+        P = pats[li]
+        dzl = np.zeros((P.n_out, B))
+        gv, gb, gx = np.zeros(nnzs[li]), np.zeros(P.n_out), np.zeros((P.n_in, B))
+        assert L.or_backward(P.n_in, P.n_out, P.rowptr, P.colidx, np.ascontiguousarray(val[li]),
+                             np.ascontiguousarray(acts[li]), B, zs[li], np.ascontiguousarray(grad), B, B, kinds[li][0],
+                             kinds[li][1], alpha, dzl, gv, gb, gx.ctypes.data, B) == 0
+        g_val[li], g_bias[li], g_in[li], grad = gv, gb, gx, gx
+    h = 1e-6
+
+    def check(analytic, perturbed_loss):
+        fd = (perturbed_loss(+h) - perturbed_loss(-h)) / (2 * h)
+        assert abs(fd - analytic) <= 1e-6 * max(1.0, abs(analytic)), (fd, analytic)
+
+    for li in range(3):
+        for p in range(nnzs[li]):
+            def f(d, li=li, p=p):
+                v2 = [v.copy() for v in val]
+                v2[li][p] += d
+                return forward(v2, bias, x)[0]
+            check(g_val[li][p], f)
+        for j in range(dims[li + 1]):
+            def f(d, li=li, j=j):
+                b2 = [b.copy() for b in bias]
+                b2[li][j] += d
+                return forward(val, b2, x)[0]
+            check(g_bias[li][j], f)
+    for i in range(dims[1]):
+        for b in range(B):
+            def f(d, i=i, b=b):
+                a1 = acts[1].copy()
+                a1[i, b] += d
+                return forward(val, bias, a1, first=1)[0]
+            check(g_in[1][i, b], f)
