@@ -78,11 +78,87 @@ static void run(const std::vector<long> &row_counts, long total_bytes)
     CHECK(hipFree(didx));
 }
 
+// Second question: would a traversal blocked by operand rows let the per-XCD L2 serve the gathers WITHOUT barriers?
+// Resident groups (the whole grid fits the chip at once) each walk the column blocks of a 128 MB operand in the same
+// order, four passes, eight random rows of the current block per step -- the access stream of a blocked forward pass of
+// the densest sweep layer (262 144 x 262 144, 3.4e7 connections, B = 128) with accumulators kept on chip.  Nothing
+// synchronises the groups; if they stayed within a block or two of each other an L2 (4 MB) would hold what they read.
+__global__ __launch_bounds__(256) void walk(const float *x, const int *idx, int ngroups, int steps, float *out)
+{
+    const int g = blockIdx.x * 8 + threadIdx.x / 32;
+    const int lane = threadIdx.x % 32;
+    if (g >= ngroups) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int *my = idx + (long)g * steps * 8;
+    for (int s = 0; s < steps; ++s) {
+        int c[8];
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) c[u] = my[s * 8 + u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = *(const float4 *)(x + (long)c[u] * 128 + lane * 4);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+    }
+    if (acc.x == 12345.f) out[g] = acc.y + acc.z + acc.w;   // never true: keeps the loads alive
+}
+
+static void run_walk()
+{
+    const int n = 262144;
+    const long total = 33554432;   // gathers per launch
+    float *x, *out;
+    int *didx;
+    CHECK(hipMalloc(&x, (size_t)n * 512));
+    CHECK(hipMemset(x, 0, (size_t)n * 512));
+    CHECK(hipMalloc(&didx, total * 4));
+    CHECK(hipMalloc(&out, 16384 * 4));
+    printf("# blocked walk without barriers: 3.4e7 gathers of 512-byte rows from a 134 MB operand by resident groups that visit its\n"
+           "# column blocks in the same order (4 passes); 1 block = no blocking\n");
+    std::vector<int> h((size_t)total);
+    for (int ngroups : {16384, 8192})
+        for (int nb : {1, 32, 64, 128, 256}) {
+            const int steps = (int)(total / 8 / ngroups);
+            const int passes = nb == 1 ? 1 : 4;
+            const int per_block = steps / (passes * nb) > 0 ? steps / (passes * nb) : 1;
+            const int bsize = n / nb;
+            std::mt19937 rng(7);
+            for (int g = 0; g < ngroups; ++g)
+                for (int s = 0; s < steps; ++s) {
+                    const int blk = nb == 1 ? 0 : (s / per_block) % nb;
+                    for (int u = 0; u < 8; ++u) h[((size_t)g * steps + s) * 8 + u] = blk * bsize + (int)(rng() % bsize);
+                }
+            CHECK(hipMemcpy(didx, h.data(), total * 4, hipMemcpyHostToDevice));
+            hipEvent_t a, b;
+            CHECK(hipEventCreate(&a));
+            CHECK(hipEventCreate(&b));
+            float best = 1e9f;
+            for (int rep = 0; rep < 4; ++rep) {
+                CHECK(hipEventRecord(a));
+                hipLaunchKernelGGL(walk, dim3(ngroups / 8), dim3(256), 0, 0, x, didx, ngroups, steps, out);
+                CHECK(hipEventRecord(b));
+                CHECK(hipEventSynchronize(b));
+                float ms;
+                CHECK(hipEventElapsedTime(&ms, a, b));
+                if (rep > 0 && ms < best) best = ms;
+            }
+            printf("%5d groups, %3d column blocks of %6.2f MB: %.3f ms, %.2f TB/s gathered\n", ngroups, nb, bsize * 512.0 / 1e6,
+                   best, total * 512.0 / best / 1e9);
+            fflush(stdout);
+            CHECK(hipEventDestroy(a));
+            CHECK(hipEventDestroy(b));
+        }
+    CHECK(hipFree(x));
+    CHECK(hipFree(out));
+    CHECK(hipFree(didx));
+}
+
 int main()
 {
     const long total = 8L << 30;   // 8 GiB gathered per launch
     run<32>({4096L, 8192L, 16384L, 65536L, 262144L, 1048576L, 4194304L}, total);
     run<8>({65536L, 262144L, 1048576L}, total / 4);
     run<64>({65536L, 262144L, 1048576L}, total);
+    run_walk();
     return 0;
 }
