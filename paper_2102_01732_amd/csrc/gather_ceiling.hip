@@ -153,6 +153,67 @@ static void run_walk()
     CHECK(hipFree(didx));
 }
 
+// Third question: what does the mix of the sparsest sweep layer (epsilon = 1: two random 512-byte row gathers per
+// 512-byte output row written, i.e. a third of the traffic in writes) reach when nothing else is done?  Each group
+// produces four consecutive output rows (as the span forward kernel does), each the sum of `fan` gathered rows.
+__global__ __launch_bounds__(256) void gather_write(const float *x, const int *idx, long nrows_out, int fan, float *y)
+{
+    const long g = (long)blockIdx.x * 8 + threadIdx.x / 32;
+    const int lane = threadIdx.x % 32;
+    const long r0 = g * 4;
+    if (r0 >= nrows_out) return;
+    float4 v[8];
+    const int *my = idx + r0 * fan;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = u < 4 * fan ? *(const float4 *)(x + (long)my[u] * 128 + lane * 4) : make_float4(0, 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        float4 a = v[r * fan];
+        if (fan == 2) { a.x += v[r * 2 + 1].x; a.y += v[r * 2 + 1].y; a.z += v[r * 2 + 1].z; a.w += v[r * 2 + 1].w; }
+        *(float4 *)(y + (r0 + r) * 128 + lane * 4) = a;
+    }
+}
+
+static void run_gather_write()
+{
+    const long n = 262144;
+    float *x, *y;
+    int *didx;
+    CHECK(hipMalloc(&x, n * 512));
+    CHECK(hipMemset(x, 0, n * 512));
+    CHECK(hipMalloc(&y, n * 512));
+    CHECK(hipMalloc(&didx, n * 2 * 4));
+    printf("# gather + write: %ld output rows of 512 bytes, each the sum of `fan` random rows of a 134 MB operand (fan = 2: the\n"
+           "# traffic mix of the epsilon = 1, B = 128 forward pass)\n", n);
+    for (int fan : {1, 2}) {
+        std::vector<int> h((size_t)n * fan);
+        std::mt19937 rng(3);
+        for (auto &v : h) v = (int)(rng() % n);
+        CHECK(hipMemcpy(didx, h.data(), h.size() * 4, hipMemcpyHostToDevice));
+        hipEvent_t a, b;
+        CHECK(hipEventCreate(&a));
+        CHECK(hipEventCreate(&b));
+        float best = 1e9f;
+        for (int rep = 0; rep < 6; ++rep) {
+            CHECK(hipEventRecord(a));
+            hipLaunchKernelGGL(gather_write, dim3((unsigned)(n / 4 / 8)), dim3(256), 0, 0, x, didx, n, fan, y);
+            CHECK(hipEventRecord(b));
+            CHECK(hipEventSynchronize(b));
+            float ms;
+            CHECK(hipEventElapsedTime(&ms, a, b));
+            if (rep > 0 && ms < best) best = ms;
+        }
+        const double bytes = (double)n * 512 * (fan + 1) + h.size() * 4.0;
+        printf("fan %d: %.4f ms, %.0f MB moved, %.2f TB/s\n", fan, best, bytes / 1e6, bytes / best / 1e9);
+        fflush(stdout);
+        CHECK(hipEventDestroy(a));
+        CHECK(hipEventDestroy(b));
+    }
+    CHECK(hipFree(x));
+    CHECK(hipFree(y));
+    CHECK(hipFree(didx));
+}
+
 int main()
 {
     const long total = 8L << 30;   // 8 GiB gathered per launch
@@ -160,5 +221,6 @@ int main()
     run<8>({65536L, 262144L, 1048576L}, total / 4);
     run<64>({65536L, 262144L, 1048576L}, total);
     run_walk();
+    run_gather_write();
     return 0;
 }
