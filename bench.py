@@ -74,8 +74,12 @@ def run_small(name, torch, np, binding, wl, dev, with_cpu):
     net.evolve(w.zeta, 1)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # one step = a forward launch per layer (+ the fix-up of the split output layer), the loss, a backward launch
+    # per layer and one update launch: these small networks are bound by the latency between dependent launches
+    launches = 2 * len(w.layers) + 3
     rec = dict(workload=name, dims=list(w.dims), steps=nb, value=w.n_samples / dt, unit="samples/s",
-               ms_per_step=dt / nb * 1e3, includes="one epoch + one SET evolution")
+               ms_per_step=dt / nb * 1e3, includes="one epoch + one SET evolution", launches_per_step=launches,
+               us_per_launch=dt / nb * 1e6 / launches, bound="latency between dependent kernel launches")
     net.close()
     if with_cpu:
         from oracle import oracle as orc
