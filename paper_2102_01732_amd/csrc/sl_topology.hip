@@ -512,14 +512,15 @@ __global__ void colptr_kernel(int n_cols, const uint32_t *key_sorted, long n, in
     }
     colptr[c] = (int)lo;
 }
-__global__ void csc_fill_kernel(long n, int n_rows, const int *rowptr, const int *rowid, const uint32_t *pos_sorted,
-                                const float *val, const float *vel, int *rowidx, int *csr_pos, float *valT, float *velT)
+// transposed view of a matrix with few, long rows: the row of a CSR slot is found by search in the row pointers
+__global__ void csc_fill_kernel(long n, int n_rows, const int *rowptr, const uint32_t *pos_sorted, const float *val,
+                                const float *vel, int *rowidx, int *csr_pos, float *valT, float *velT)
 {
     const long q = (long)blockIdx.x * TB + threadIdx.x;
     if (q >= n) return;
     const int p = (int)pos_sorted[q];
     csr_pos[q] = p;
-    rowidx[q] = rowid ? rowid[p] : row_of(rowptr, n_rows, p);
+    rowidx[q] = row_of(rowptr, n_rows, p);
     valT[q] = val[p];
     velT[q] = vel[p];
 }
@@ -712,8 +713,8 @@ int topo_finalize(sl_layer *L, hipStream_t s, bool packed_ready)
                                    L->csr_pos, L->valT, L->velT);
             } else {
                 // few, long rows: the row of a CSR slot is found by search in the row pointers
-                hipLaunchKernelGGL(csc_fill_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, n_out, L->rowptr, (const int *)nullptr,
-                                   vs, L->val, L->vel, L->rowidx, L->csr_pos, L->valT, L->velT);
+                hipLaunchKernelGGL(csc_fill_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, n_out, L->rowptr, vs, L->val, L->vel,
+                                   L->rowidx, L->csr_pos, L->valT, L->velT);
             }
         }
         hipLaunchKernelGGL(colptr_kernel, dim3(nblk(n_in + 1)), dim3(TB), 0, s, n_in, ks, (long)n, L->colptr);

@@ -379,7 +379,8 @@ struct BwdArgs {
     long ldp;
     int B;
     int ragged;      // B % 4 != 0
-    int tile0, tile1; // bwd_pair_kernel: the batch tiles this launch covers
+    int tile0, tile1; // the batch tiles this launch covers
+    int slice_tiles;  // host only: > 0 = one launch per this many tiles (operands sliced for L2 residency)
     Epi epi;         // SPMM, not split: what to do with the finished grad_x row
     // Update fused behind the SDDMM (eq. 1 applied where the gradient entry is produced): on the last batch
     // tile the lane that holds a finished gradient entry also holds (or fetches) that connection's weight
@@ -447,7 +448,7 @@ __global__ __launch_bounds__(BLOCK) void bwd_kernel(BwdArgs a)
     const int p0 = a.vptr[v], p1 = a.vptr[v + 1];
     const long row = a.v2row ? a.v2row[v] : v;
     const int sub = lane & (U - 1);
-    for (int tile = 0; tile * 4 * G < a.B; ++tile) {
+    for (int tile = a.tile0; tile < a.tile1; ++tile) {   // the batch tiles of this launch (all of them, or one slice)
         const int c = (tile * G + lane) * 4;
         const bool active = c < a.B;
         const bool upd = UPD && tile + 1 == a.n_tiles;   // last batch tile: the gradient entries are final
@@ -852,6 +853,13 @@ static void dispatch_g(int G, F &&f)
     }
 }
 
+// the gathered operand of a CSR-ordered pass over L (its input x): rows used very many times each, and a 32-column slice
+// of a few MB
+static bool sliceable_operand(const sl_layer *L, const SegMat &m)
+{
+    return !m.split && (long)L->cfg.n_in * 128 <= (8L << 20) && L->nnz >= 64 * L->cfg.n_in;
+}
+
 static unsigned groups_to_blocks(long n_groups, int G) { return (unsigned)((n_groups + BLOCK / G - 1) / (BLOCK / G)); }
 
 static void set_dropout(Epi &e, const sl_layer *owner)
@@ -889,7 +897,13 @@ int launch_forward(sl_layer *L, const float *x, int64_t ldx, int B, float *a, in
                    float *part)
 {
     const SegMat &m = L->fwd;
-    const int G = group_width(B), U = chunk_width(m, L->nnz);
+    int G = group_width(B);
+    // An operand whose rows are each gathered very many times and whose 32-column slice (128 bytes per row) is a
+    // few MB -- the 65 536-feature input block of the 10^6-neuron network: 8 MB per slice, every row used 160
+    // times -- is walked one 32-column slice after the other (batch tiles in grid.y are dispatched in order), so
+    // that an L2 serves a good part of the gathers.  Same arithmetic per element in the same order: same bits.
+    if (G > 8 && sliceable_operand(L, m)) G = 8;
+    const int U = chunk_width(m, L->nnz);
     const int tiles = (B + 4 * G - 1) / (4 * G);
     FwdArgs f;
     f.vptr = m.vptr; f.v2row = m.v2row; f.nv = m.nv; f.idx = m.idx; f.w = L->val; f.x = x; f.ldx = (int)ldx;
@@ -1000,10 +1014,16 @@ static void launch_bwd_kernel_u(int G, int U, int B, int nv, BwdArgs b, hipStrea
         }
         return;
     }
-    dispatch_gu(G, U, [&](auto g, auto u) {
-        constexpr int GG = decltype(g)::value, UU = decltype(u)::value;
-        hipLaunchKernelGGL((bwd_kernel<GG, UU, SPMM, UPD>), dim3(groups_to_blocks(nv, GG)), dim3(BLOCK), 0, s, b);
-    });
+    const int tiles = b.tile1;
+    const int per_launch = b.slice_tiles > 0 ? b.slice_tiles : tiles;   // slice_tiles: one launch per that many tiles
+    for (int t0 = 0; t0 < tiles; t0 += per_launch) {
+        b.tile0 = t0;
+        b.tile1 = min(t0 + per_launch, tiles);
+        dispatch_gu(G, U, [&](auto g, auto u) {
+            constexpr int GG = decltype(g)::value, UU = decltype(u)::value;
+            hipLaunchKernelGGL((bwd_kernel<GG, UU, SPMM, UPD>), dim3(groups_to_blocks(nv, GG)), dim3(BLOCK), 0, s, b);
+        });
+    }
 }
 // Batches above 256 columns take two tiles per pass with half the chunk width (the same number of row
 // gathers in flight per lane).
@@ -1031,7 +1051,7 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
     L->dz_ready = 0;
     BwdArgs b;
     b.B = B; b.g = L->grad; b.ragged = (B % 4) != 0; b.part = nullptr; b.ldp = L->ldz;
-    b.upd_mode = L->fuse_mode; b.n_tiles = (B + 4 * G - 1) / (4 * G);
+    b.upd_mode = L->fuse_mode; b.n_tiles = (B + 4 * G - 1) / (4 * G); b.slice_tiles = 0;
     b.upd_w = L->has_csc ? L->valT : L->val; b.upd_vel = L->has_csc ? L->velT : L->vel;
     b.upd_pos = L->has_csc ? L->csr_pos : nullptr; b.upd_w_csr = L->val;
     b.lr = L->cfg.lr; b.mu = L->cfg.momentum; b.wd = L->cfg.weight_decay;
@@ -1061,8 +1081,14 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
         b.vptr = m.vptr; b.v2row = m.v2row; b.nv = m.nv; b.idx = m.idx; b.w = nullptr;
         b.held = L->dz; b.ldh = L->ldz; b.gath = x; b.ldga = (int)ldx;
         b.epi = Epi();
+        int Gs = G;
+        if (G > 8 && B <= 256 && sliceable_operand(L, m)) {   // as in the forward pass: one 32-column slice per launch
+            Gs = 8;
+            b.slice_tiles = 1;
+            b.n_tiles = (B + 31) / 32;
+        }
         ProfScope ps(L, K_SDDMM, s);
-        launch_bwd_kernel<false>(G, U, B, m.nv, b, s);
+        launch_bwd_kernel<false>(Gs, U, B, m.nv, b, s);
     }
     SL_HIP(L, hipGetLastError());
     L->weights_updated = L->fuse_mode != 0;
