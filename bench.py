@@ -134,14 +134,20 @@ def main():
 
     if args.evolve_only > 0:
         net = binding.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=B)
-        times = []
+        times, serial = [], []
         for g in range(args.evolve_only):
             torch.cuda.synchronize()
             q0 = time.perf_counter()
-            net.evolve(w.zeta, g + 1)
+            net.evolve(w.zeta, 2 * g + 1)
             torch.cuda.synchronize()
             times.append((time.perf_counter() - q0) * 1e3)
-        print(json.dumps(dict(workload=args.workload, evolve_ms_all_layers=times, connections=sum(s.nnz for s in w.layers))))
+            q0 = time.perf_counter()
+            for layer in net.layers:
+                layer.evolve(w.zeta, 2 * g + 2)
+            torch.cuda.synchronize()
+            serial.append((time.perf_counter() - q0) * 1e3)
+        print(json.dumps(dict(workload=args.workload, evolve_ms_all_layers=times, evolve_ms_layer_after_layer=serial,
+                              connections=sum(s.nnz for s in w.layers))))
         return
 
     # ---- synthetic data, resident in HBM, feature-major minibatch blocks [n_blocks][n_in][B]
@@ -202,11 +208,19 @@ def main():
     net.evolve(w.zeta, generation[0])
     torch.cuda.synchronize()
     evolve_ms = (time.perf_counter() - te0) * 1e3
+    generation[0] += 1
+    ts0 = time.perf_counter()
+    for layer in net.layers:
+        layer.evolve(w.zeta, generation[0])
+    torch.cuda.synchronize()
+    evolve_serial_ms = (time.perf_counter() - ts0) * 1e3
     ev_bytes = sum(evolve_bytes(spec, li > 0) for li, spec in enumerate(w.layers))
     evolve = dict(ms_all_layers=evolve_ms, connections=sum(s.nnz for s in w.layers), model_bytes=ev_bytes,
                   model_gbs=ev_bytes / evolve_ms / 1e6, frac=ev_bytes / evolve_ms / 1e6 / HBM_PEAK_GBS,
                   share_of_an_epoch=evolve_ms / (evolve_ms + n_blocks * elapsed / K * 1e3),
-                  note="host wall clock around sparse_layer_evolve of every layer, synchronisations included")
+                  ms_layer_after_layer=evolve_serial_ms,
+                  note="host wall clock around sparse_layers_evolve (the layers' cycles run concurrently, one stream each), "
+                       "synchronisations included; ms_layer_after_layer: one sparse_layer_evolve call per layer instead")
 
     # ---- per-kernel durations with HIP events on the launch stream
     for layer in net.layers:
@@ -307,7 +321,7 @@ def main():
         twin = binding.SparseLayer(binding.make_config(
             spec1.n_in, spec1.n_out, nnz=spec1.nnz, act_kind=spec1.act_kind, act_parity=spec1.act_parity, alpha=w.alpha,
             init_limit=spec1.init_limit, lr=w.lr, momentum=w.momentum, seed=w.seed + 1, layer_id=spec1.layer_id,
-            max_batch=B, need_input_grad=True), scratch=net.scratch)
+            max_batch=B, need_input_grad=True), scratch=net.layers[1].scratch)
         torch.cuda.synchronize()
         ta0 = time.perf_counter()
         binding.average_layers(twin, [twin, net.layers[1]])

@@ -155,6 +155,16 @@ int sparse_layer_set_fused_update(sl_layer *layer, int32_t mode);
  * view.  nnz is unchanged.  k = floor(zeta*nnz + 0.5) in double.  Synchronises the stream. */
 int sparse_layer_evolve(sl_layer *layer, double zeta, uint64_t generation, void *hip_stream);
 
+/* sparse_layer_evolve for up to 16 layers at once (Algorithm 2 evolves every layer after an epoch, and the layers'
+ * cycles are independent of each other): layer k runs on hip_streams[k] (host array of `count` stream handles, any
+ * of them may be the null stream) from a host thread of its own, so that one layer's waits overlap the others'
+ * kernels.  Every layer ends exactly as after its own sparse_layer_evolve call.  The layers must have been
+ * initialised with scratch buffers that do not overlap (SL_EINVAL otherwise).  The caller orders each stream after
+ * the work that produced the layer's weights; all streams are synchronised on return.  Returns the first non-zero
+ * code in layer order (that layer holds the message; the other layers still complete their cycle). */
+int sparse_layers_evolve(sl_layer *const *layers, int32_t count, double zeta, uint64_t generation,
+                         void *const *hip_streams);
+
 /* Regrowth sampler of sparse_layer_evolve (sparse layers only).  Candidate positions t = 0, 1, 2, ... are
  * evaluated a window [0, W) at a time; a window that accepts fewer than k positions is evaluated again twice as
  * long.  first_window: W of the first attempt (0: chosen from the expected number of draws plus eight standard

@@ -29,7 +29,7 @@ EXPORTS = [
     "sparse_layer_infer", "sparse_layers_average_query", "sparse_layers_average",
     "sparse_loss_softmax_ce_into", "sparse_layers_update", "sparse_layer_set_dropout",
     "sparse_layer_retain_valid_updates", "sparse_layer_infer_static",
-    "sparse_layer_set_fused_update", "sparse_layer_set_sampler_window",
+    "sparse_layer_set_fused_update", "sparse_layer_set_sampler_window", "sparse_layers_evolve",
 ]
 N_KERNEL_IDS = 7
 
@@ -81,6 +81,7 @@ def lib():
         L.sparse_layers_average.argtypes = [vp, C.POINTER(vp), i32, vp, C.c_size_t, vp]
         L.sparse_loss_softmax_ce_into.argtypes = [vp, f32p, i64, i32p, i32, f32p, vp]
         L.sparse_layers_update.argtypes = [C.POINTER(vp), i32, vp]
+        L.sparse_layers_evolve.argtypes = [C.POINTER(vp), i32, C.c_double, C.c_uint64, C.POINTER(vp)]
         L.sparse_layer_set_dropout.argtypes = [vp, C.c_float, C.c_uint64]
         L.sparse_layer_importance.argtypes = [vp, vp]
         L.sparse_layer_retain_valid_updates.argtypes = [vp, i32p, i32p, f32p, i64, f32p, vp]
@@ -295,7 +296,9 @@ class SparseMLP:
     library; activations and gradients are preallocated feature-major buffers [n][ld]."""
 
     def __init__(self, layer_specs: Sequence, *, alpha: float, lr: float, momentum: float, seed: int, max_batch: int,
-                 prune_mode: int = 0, weight_decay: float = 0.0, device="cuda:0"):
+                 prune_mode: int = 0, weight_decay: float = 0.0, device="cuda:0", shared_scratch: bool = False):
+        """shared_scratch: one scratch buffer (the largest layer's) serves all layers and `evolve` takes the
+        layers one after the other; by default every layer has its own and they evolve concurrently."""
         self.device = torch.device(device)
         self.max_batch = max_batch
         self.ld = (max_batch + 31) // 32 * 32
@@ -303,9 +306,14 @@ class SparseMLP:
                             init_limit=s.init_limit, lr=lr, momentum=momentum, weight_decay=weight_decay, seed=seed,
                             layer_id=s.layer_id, max_batch=max_batch, prune_mode=prune_mode,
                             need_input_grad=(li > 0)) for li, s in enumerate(layer_specs)]
-        scratch_bytes = max(query_sizes(c)[1] for c in cfgs)
-        self.scratch = torch.empty(scratch_bytes + 256, dtype=torch.uint8, device=self.device)
-        self.layers: List[SparseLayer] = [SparseLayer(c, device, self.scratch) for c in cfgs]
+        self.shared_scratch = shared_scratch
+        if shared_scratch:
+            scratch_bytes = max(query_sizes(c)[1] for c in cfgs)
+            self.scratch = torch.empty(scratch_bytes + 256, dtype=torch.uint8, device=self.device)
+            self.layers: List[SparseLayer] = [SparseLayer(c, device, self.scratch) for c in cfgs]
+        else:
+            self.layers = [SparseLayer(c, device) for c in cfgs]
+            self._evolve_streams = [torch.cuda.Stream(device=self.device) for _ in cfgs]
         self.acts = [torch.zeros((s.n_out, self.ld), dtype=torch.float32, device=self.device) for s in layer_specs]
         # Layers are chained: each backward hands dz to the layer below inside its own kernel, so only
         # the output layer needs a gradient buffer.
@@ -371,8 +379,18 @@ class SparseMLP:
         last._check(lib().sparse_layers_update(self._handles, n, _stream()), "sparse_layers_update")
 
     def evolve(self, zeta: float, generation: int):
-        for layer in self.layers:
-            layer.evolve(zeta, generation)
+        if self.shared_scratch or len(self.layers) == 1:
+            for layer in self.layers:
+                layer.evolve(zeta, generation)
+            return
+        cur = torch.cuda.current_stream()
+        for st in self._evolve_streams:
+            st.wait_stream(cur)
+        streams = (C.c_void_p * len(self.layers))(*[st.cuda_stream for st in self._evolve_streams])
+        rc = lib().sparse_layers_evolve(self._handles, len(self.layers), float(zeta), int(generation), streams)
+        if rc != SL_OK:   # the layer that failed holds the message
+            msgs = [lib().sparse_layer_last_error(l.handle).decode() for l in self.layers]
+            raise SparseSetError(rc, "sparse_layers_evolve", "; ".join(m for m in msgs if m))
 
     def fit(self, blocks: torch.Tensor, labels: torch.Tensor, sizes: Sequence[int], epochs: int, zeta: float, *,
             importance_every: int = 0, importance_start: int = 0, importance_quantile: float = 0.0,

@@ -6,6 +6,8 @@
 #include <string.h>
 
 #include <new>
+#include <thread>
+#include <vector>
 
 #include "sl_internal.h"
 
@@ -100,7 +102,6 @@ int plan_state(const sl_config &c, int64_t nnz, StatePlan *sp)
         sp->b_v2row = take(cur, 4 * (size_t)sp->nv_cap_b);
         sp->b_rvptr = take(cur, 4 * (ni + 1));
     }
-    sp->rowid = take(cur, 4 * n);
     sp->sel = take(cur, 2 * sizeof(SelState));
     sp->total = cur;
     return SL_OK;
@@ -147,7 +148,6 @@ int plan_scratch(const sl_config &c, int64_t nnz, ScratchPlan *cp)
     cp->temp_bytes = ((size_t)32 << 20) + 2 * (w > n ? w : n);
     cp->temp = take(cur, cp->temp_bytes);
     cp->small = take(cur, 1024);
-    cp->s_row = take(cur, 4 * n);
     cp->packed = take(cur, csc ? 16 * n : 0);   // (row, weight, velocity) per CSR slot while the transposed view is rebuilt
     cp->total = cur > train_end ? cur : train_end;
     return SL_OK;
@@ -233,7 +233,6 @@ int sparse_layer_init(const sl_config *cfg, void *state_dev, size_t state_bytes,
     L->mask = (uint8_t *)(b + sp.mask); L->dz = (float *)(b + sp.dz);
     L->fwd.vptr_store = (int *)(b + sp.f_vptr); L->fwd.v2row_store = (int *)(b + sp.f_v2row);
     L->fwd.rvptr_store = (int *)(b + sp.f_rvptr); L->fwd.nv_cap = sp.nv_cap_f;
-    L->rowid = (int *)(b + sp.rowid);
     L->sel = (SelState *)(b + sp.sel);
     hipStream_t s = (hipStream_t)hip_stream;
     L->last_stream = s;
@@ -397,6 +396,36 @@ int sparse_layer_evolve(sl_layer *L, double zeta, uint64_t generation, void *hip
     if (e != hipSuccess) return set_err(L, SL_EHIP, "evolve: %s", hipGetErrorString(e));
     L->phase = 0;
     L->weights_updated = false;
+    return SL_OK;
+}
+
+int sparse_layers_evolve(sl_layer *const *layers, int32_t count, double zeta, uint64_t generation, void *const *hip_streams)
+{
+    if (!layers || !hip_streams || count < 1 || count > SL_MAX_MULTI) return SL_EINVAL;
+    for (int k = 0; k < count; ++k) {
+        if (!layers[k]) return SL_EINVAL;
+        for (int j = 0; j < k; ++j) {
+            const char *a = layers[j]->scratch, *b = layers[k]->scratch;
+            if (layers[j] == layers[k] || (a < b + layers[k]->scratch_bytes && b < a + layers[j]->scratch_bytes))
+                return set_err(layers[k], SL_EINVAL, "layers %d and %d share a scratch buffer: they cannot evolve concurrently", j, k);
+        }
+    }
+    int dev = 0;
+    SL_HIP(layers[0], hipGetDevice(&dev));
+    // The cycles of different layers touch nothing in common; each runs from a host thread of its own so that the
+    // waits of one layer (survivor count, accepted candidates, longest row) overlap the kernels of the others.
+    std::vector<int> rc((size_t)count, SL_OK);
+    std::vector<std::thread> workers;
+    for (int k = 1; k < count; ++k)
+        workers.emplace_back([&, k] {
+            hipError_t e = hipSetDevice(dev);
+            rc[k] = e != hipSuccess ? set_err(layers[k], SL_EHIP, "hipSetDevice: %s", hipGetErrorString(e))
+                                    : sparse_layer_evolve(layers[k], zeta, generation, hip_streams[k]);
+        });
+    rc[0] = sparse_layer_evolve(layers[0], zeta, generation, hip_streams[0]);
+    for (auto &w : workers) w.join();
+    for (int k = 0; k < count; ++k)
+        if (rc[k]) return rc[k];
     return SL_OK;
 }
 

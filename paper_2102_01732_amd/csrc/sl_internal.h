@@ -38,7 +38,7 @@ struct ScratchPlan {
     size_t partial = 0;
     // evolve / init
     size_t tie64 = 0, trank = 0, keep = 0, kscan = 0, s_col = 0, s_val = 0, s_vel = 0, rowptr_s = 0, new_p = 0;
-    size_t keyA = 0, keyB = 0, payA = 0, payB = 0, f0 = 0, f1 = 0, f2 = 0, f3 = 0, temp = 0, small = 0, packed = 0, s_row = 0;
+    size_t keyA = 0, keyB = 0, payA = 0, payB = 0, f0 = 0, f1 = 0, f2 = 0, f3 = 0, temp = 0, small = 0, packed = 0;
     size_t temp_bytes = 0;
     int64_t w_cap = 0;   // capacity of the sampler window (items)
     int dense_mode = 0;  // sampler mode of this layer (fixed: |occupied| + k == nnz always)
@@ -47,7 +47,7 @@ struct ScratchPlan {
 struct StatePlan {
     size_t total = 0;
     size_t rowptr = 0, colidx = 0, val = 0, vel = 0, grad = 0, bias = 0, bias_vel = 0, grad_bias = 0;
-    size_t colptr = 0, rowidx = 0, csr_pos = 0, valT = 0, velT = 0, rowid = 0;
+    size_t colptr = 0, rowidx = 0, csr_pos = 0, valT = 0, velT = 0;
     size_t mask = 0, dz = 0;
     size_t f_vptr = 0, f_v2row = 0, f_rvptr = 0, b_vptr = 0, b_v2row = 0, b_rvptr = 0;
     size_t sel = 0;
@@ -75,7 +75,6 @@ struct sl_layer {
     // CSR of Wt (forward orientation); val is always current.  vel/grad are in CSR order when
     // the layer has no CSC view; with a CSC view the master copies are valT/velT/grad in CSC order.
     int *rowptr = nullptr, *colidx = nullptr;
-    int *rowid = nullptr;   // row of every CSR slot (matrices with many short rows only; kept current by every rebuild)
     float *val = nullptr, *vel = nullptr, *grad = nullptr, *bias = nullptr, *bias_vel = nullptr, *grad_bias = nullptr;
     int *colptr = nullptr, *rowidx = nullptr, *csr_pos = nullptr;
     float *valT = nullptr, *velT = nullptr;
@@ -176,7 +175,7 @@ int launch_update_many(sl_layer *const *layers, int count, hipStream_t s);
 // topology (sl_topology.hip)
 int topo_init(sl_layer *L, hipStream_t s);
 int topo_evolve(sl_layer *L, double zeta, uint32_t generation, hipStream_t s);
-int topo_finalize(sl_layer *L, hipStream_t s, bool packed_ready = false);   // vrows + CSC view from the CSR arrays
+int topo_finalize(sl_layer *L, hipStream_t s, bool from_merge = false);   // vrows + CSC view from the CSR arrays
 int topo_sync_csr_vel(sl_layer *L, hipStream_t s);    // CSC-master layers: velT -> vel (CSR order)
 int topo_sync_csr_grad(sl_layer *L, float *grad_csr_dev, hipStream_t s);
 int topo_check_temp(sl_layer *L, hipStream_t s);      // rocPRIM temporaries fit the reservation

@@ -230,7 +230,7 @@ __global__ void keep_flag_kernel(const float *val, long n, int mode, const SelSt
 }
 
 __global__ void compact_kernel(long n, const uint32_t *keep, const uint32_t *kscan, const int *col, const float *val,
-                               const float *vel, const int *rowid, int *s_col, float *s_val, float *s_vel, int *s_row)
+                               const float *vel, int *s_col, float *s_val, float *s_vel)
 {
     const long p = (long)blockIdx.x * TB + threadIdx.x;
     if (p >= n || !keep[p]) return;
@@ -238,7 +238,6 @@ __global__ void compact_kernel(long n, const uint32_t *keep, const uint32_t *ksc
     s_col[d] = col[p];
     s_val[d] = val[p];
     s_vel[d] = vel[p];
-    if (rowid) s_row[d] = rowid[p];
 }
 
 __global__ void survivor_rowptr_kernel(int n_rows, const int *rowptr, const uint32_t *kscan, int *rowptr_s)
@@ -364,80 +363,114 @@ __global__ void merge_rowptr_kernel(int n_rows, uint32_t n_in, const int *rowptr
     if (r > n_rows) return;
     rowptr[r] = rowptr_s[r] + (int)lower_bound_u64(new_p, k, (uint64_t)r * n_in);
 }
-__global__ void merge_survivor_kernel(long ns, int n_rows, uint32_t n_in, const int *rowptr_s, const int *s_col,
-                                      const float *s_val, const float *s_vel, const uint64_t *new_p, long k,
-                                      int *col, float *val, float *vel)
-{
-    const long s = (long)blockIdx.x * TB + threadIdx.x;
-    if (s >= ns) return;
-    const int j = row_of(rowptr_s, n_rows, (int)s);
-    const int i = s_col[s];
-    const long d = s + lower_bound_u64(new_p, k, (uint64_t)j * n_in + (uint64_t)i);
-    col[d] = i;
-    val[d] = s_val[s];
-    vel[d] = s_vel[s];
-}
-__global__ void merge_new_kernel(long k, uint32_t n_in, const int *rowptr_s, const int *s_col, const uint64_t *new_p,
-                                 Rng r, float limit, int *col, float *val, float *vel)
-{
-    const long t = (long)blockIdx.x * TB + threadIdx.x;
-    if (t >= k) return;
-    const uint64_t p = new_p[t];
-    const int j = (int)(p / n_in), i = (int)(p % n_in);
-    const long d = t + lower_bound_i32(s_col, rowptr_s[j], rowptr_s[j + 1], i);
-    col[d] = i;
-    val[d] = fresh_weight(r, p, limit);
-    vel[d] = 0.f;
-}
-
-// Matrices with many short rows (every Erdos-Renyi layer) keep the row of every CSR slot (rowid), so a survivor
-// finds its new slot with a short scan over its own row's new connections instead of two binary searches over
-// whole arrays.  The merge also leaves (row, weight, velocity) of every CSR slot packed in 16 bytes for the
-// rebuild of the transposed view, which then needs one 16-byte gather per connection instead of three 4-byte
-// gathers from three arrays.
+// The new CSR is written front to back, eight consecutive slots per thread, so that every array is stored once in
+// whole cache lines.  A thread finds the row of its first slot by a search among the few rows that its tile of
+// MERGE_TILE slots touches (merge_tile_rows_kernel finds them); inside the row the survivors and the new connections
+// are both ascending by column, and the slot's rank in their union says how many of each precede it (a bisection).
+// From there the thread walks: the next slot takes the smaller of the next survivor and the next new connection,
+// and both cursors run on through the following rows, whose entries follow in the same two arrays.
+// The merge also leaves (row, weight, velocity) of every slot packed in 16 bytes for the rebuild of the transposed
+// view, which then needs one 16-byte gather per connection, and (KEYS) the (column, slot) pairs that view is sorted from.
 struct __align__(16) RowValVel { int row; float val; float vel; int pad; };
+constexpr int MERGE_RUN = 8;                    // consecutive slots per thread
+constexpr int MERGE_TILE = MERGE_RUN * TB;      // slots per block
 
-__global__ void merge_survivor_rows_kernel(long ns, uint32_t n_in, const int *rowptr_s, const int *s_row, const int *s_col,
-                                           const float *s_val, const float *s_vel, const uint64_t *new_p, const int *rowptr,
-                                           int *col, float *val, float *vel, int *rowid, RowValVel *packed)
+__global__ void merge_tile_rows_kernel(long n_tiles, int n_rows, const int *rowptr, long nnz, int2 *tile_rows)
 {
-    const long sp = (long)blockIdx.x * TB + threadIdx.x;
-    if (sp >= ns) return;
-    const int j = s_row[sp], i = s_col[sp];
-    const int s0 = rowptr_s[j], d0 = rowptr[j];
-    const long t0 = (long)d0 - s0;                                             // new connections in the rows before row j
-    const int cnt = (rowptr[j + 1] - d0) - (rowptr_s[j + 1] - s0);             // new connections of row j
-    const uint64_t me = (uint64_t)j * n_in + (uint64_t)i;
-    int r = 0;                                                                 // those of them left of this survivor
-    while (r < cnt && new_p[t0 + r] < me) ++r;
-    const long d = (long)d0 + (sp - s0) + r;
-    const float w = s_val[sp], v = s_vel[sp];
-    col[d] = i; val[d] = w; vel[d] = v;
-    rowid[d] = j;
-    if (packed) packed[d] = RowValVel{j, w, v, 0};
+    const long b = (long)blockIdx.x * TB + threadIdx.x;
+    if (b >= n_tiles) return;
+    const long first = b * MERGE_TILE, last = min(first + MERGE_TILE, nnz) - 1;
+    tile_rows[b] = make_int2(row_of(rowptr, n_rows, (int)first), row_of(rowptr, n_rows, (int)last));
 }
-// the new connections of such a matrix: as merge_new_kernel, and the row id / packed copy as above
-__global__ void merge_new_rows_kernel(long k, uint32_t n_in, const int *rowptr_s, const int *s_col, const uint64_t *new_p,
-                                      Rng r, float limit, int *col, float *val, float *vel, int *rowid, RowValVel *packed)
+
+template <bool KEYS>
+__global__ __launch_bounds__(TB) void merge_rows_kernel(long nnz, uint32_t n_in, const int2 *tile_rows, const int *rowptr_s,
+                                                        const int *rowptr, const int *s_col, const float *s_val,
+                                                        const float *s_vel, const uint64_t *new_p, Rng rng, float limit,
+                                                        int *col, float *val, float *vel, RowValVel *packed, uint32_t *key,
+                                                        uint32_t *pay)
 {
-    const long t = (long)blockIdx.x * TB + threadIdx.x;
-    if (t >= k) return;
-    const uint64_t p = new_p[t];
-    const int j = (int)(p / n_in), i = (int)(p % n_in);
-    const long d = t + lower_bound_i32(s_col, rowptr_s[j], rowptr_s[j + 1], i);
-    const float w = fresh_weight(r, p, limit);
-    col[d] = i; val[d] = w; vel[d] = 0.f;
-    rowid[d] = j;
-    if (packed) packed[d] = RowValVel{j, w, 0.f, 0};
+    const long d_first = (long)blockIdx.x * MERGE_TILE + (long)threadIdx.x * MERGE_RUN;
+    if (d_first >= nnz) return;
+    const int2 jr = tile_rows[blockIdx.x];
+    int lo = jr.x, hi = jr.y;                          // the last row that starts at or before the first slot
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (rowptr[mid] <= d_first) lo = mid; else hi = mid - 1;
+    }
+    int j = lo;
+    long sa, tb;                                       // cursors: next survivor, next new connection
+    int s_end, row_end;                                // end of row j in the survivor array and in the new CSR
+    {
+        const int d0 = rowptr[j], s0 = rowptr_s[j];
+        s_end = rowptr_s[j + 1];
+        row_end = rowptr[j + 1];
+        const int na = s_end - s0, nb = (row_end - d0) - na;
+        const long t0 = (long)d0 - s0;
+        const int m = (int)(d_first - d0);             // rank of the first slot in its row
+        const uint64_t base = (uint64_t)j * n_in;
+        int a_lo = max(0, m - nb), a_hi = min(m, na);  // a = survivors among the m connections left of the slot
+        while (a_lo < a_hi) {
+            const int mid = (a_lo + a_hi) >> 1;
+            if ((uint64_t)s_col[s0 + mid] < new_p[t0 + (m - mid - 1)] - base) a_lo = mid + 1; else a_hi = mid;
+        }
+        sa = s0 + a_lo;
+        tb = t0 + (m - a_lo);
+    }
+    const int run = (int)min((long)MERGE_RUN, nnz - d_first);
+    int ci[MERGE_RUN], rj[MERGE_RUN];
+    float cw[MERGE_RUN], cv[MERGE_RUN];
+#pragma unroll
+    for (int u = 0; u < MERGE_RUN; ++u) {
+        ci[u] = 0; rj[u] = 0; cw[u] = 0.f; cv[u] = 0.f;
+        if (u < run) {
+            while (d_first + u >= row_end) {           // on to the next row that has a slot (empty rows are skipped)
+                ++j;
+                s_end = rowptr_s[j + 1];
+                row_end = rowptr[j + 1];
+            }
+            const long t_end = (long)row_end - s_end;  // end of row j among the new connections
+            const uint64_t base = (uint64_t)j * n_in;
+            const int ca = sa < s_end ? s_col[sa] : 0;
+            const uint64_t pb = tb < t_end ? new_p[tb] : 0;
+            const bool survivor = sa < s_end && (tb >= t_end || (uint64_t)ca < pb - base);
+            rj[u] = j;
+            if (survivor) { ci[u] = ca; cw[u] = s_val[sa]; cv[u] = s_vel[sa]; ++sa; }
+            else { ci[u] = (int)(pb - base); cw[u] = fresh_weight(rng, pb, limit); ++tb; }
+        }
+    }
+    if (run == MERGE_RUN) {
+#pragma unroll
+        for (int h = 0; h < MERGE_RUN; h += 4) {
+            *(int4 *)(col + d_first + h) = make_int4(ci[h], ci[h + 1], ci[h + 2], ci[h + 3]);
+            *(float4 *)(val + d_first + h) = make_float4(cw[h], cw[h + 1], cw[h + 2], cw[h + 3]);
+            *(float4 *)(vel + d_first + h) = make_float4(cv[h], cv[h + 1], cv[h + 2], cv[h + 3]);
+            if (KEYS) {
+                *(uint4 *)(key + d_first + h) = make_uint4(ci[h], ci[h + 1], ci[h + 2], ci[h + 3]);
+                const uint32_t q = (uint32_t)(d_first + h);
+                *(uint4 *)(pay + d_first + h) = make_uint4(q, q + 1, q + 2, q + 3);
+            }
+        }
+        if (packed) {
+#pragma unroll
+            for (int u = 0; u < MERGE_RUN; ++u) packed[d_first + u] = RowValVel{rj[u], cw[u], cv[u], 0};
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < MERGE_RUN; ++u)
+            if (u < run) {
+                const long d = d_first + u;
+                col[d] = ci[u]; val[d] = cw[u]; vel[d] = cv[u];
+                if (packed) packed[d] = RowValVel{rj[u], cw[u], cv[u], 0};
+                if (KEYS) { key[d] = (uint32_t)ci[u]; pay[d] = (uint32_t)d; }
+            }
+    }
 }
-__global__ void pack_rows_kernel(int n_rows, const int *ptr, const float *val, const float *vel, int *rowid, RowValVel *packed)
+__global__ void pack_rows_kernel(int n_rows, const int *ptr, const float *val, const float *vel, RowValVel *packed)
 {
     const int r = blockIdx.x * TB + threadIdx.x;
     if (r >= n_rows) return;
-    for (int p = ptr[r]; p < ptr[r + 1]; ++p) {
-        rowid[p] = r;
-        if (packed) packed[p] = RowValVel{r, val[p], vel[p], 0};
-    }
+    for (int p = ptr[r]; p < ptr[r + 1]; ++p) packed[p] = RowValVel{r, val[p], vel[p], 0};
 }
 __global__ void csc_fill_packed_kernel(long n, const uint32_t *pos_sorted, const RowValVel *packed, int *rowidx, int *csr_pos,
                                        float *valT, float *velT)
@@ -689,8 +722,9 @@ static int finish_vrows(sl_layer *L, SegMat &m, int nnz, int maxlen, hipStream_t
     return SL_OK;
 }
 
-// packed_ready: the caller has already left (row, weight, velocity) of every CSR slot in the `packed` scratch region
-int topo_finalize(sl_layer *L, hipStream_t s, bool packed_ready)
+// from_merge: the merge has already left (row, weight, velocity) of every CSR slot in the `packed` scratch region and
+// the (column, slot) pairs in the sort's input buffers
+int topo_finalize(sl_layer *L, hipStream_t s, bool from_merge)
 {
     const int n = (int)L->nnz, n_in = (int)L->cfg.n_in, n_out = (int)L->cfg.n_out;
     L->fwd.n_rows = n_out; L->fwd.ptr = L->rowptr; L->fwd.idx = L->colidx;
@@ -701,14 +735,15 @@ int topo_finalize(sl_layer *L, hipStream_t s, bool packed_ready)
         uint32_t *vA = at<uint32_t>(L, L->cp.payA), *vB = at<uint32_t>(L, L->cp.payB);
         uint32_t *ks = kA, *vs = vA;
         if (n > 0) {
-            hipLaunchKernelGGL(iota_copy_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, L->colidx, kA, vA);
+            if (!from_merge)
+                hipLaunchKernelGGL(iota_copy_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, L->colidx, kA, vA);
             SL_HIP(L, sort_pairs<uint32_t>(at<char>(L, L->cp.temp), L->cp.temp_bytes, kA, kB, vA, vB, (size_t)n,
                                            bit_length((uint64_t)n_in - 1), &ks, &vs, s));
-            if (short_rows(L)) {
+            if (from_merge || short_rows(L)) {
                 RowValVel *packed = at<RowValVel>(L, L->cp.packed);
-                if (!packed_ready)
+                if (!from_merge)
                     hipLaunchKernelGGL(pack_rows_kernel, dim3(nblk(n_out)), dim3(TB), 0, s, n_out, L->rowptr, L->val, L->vel,
-                                       L->rowid, packed);
+                                       packed);
                 hipLaunchKernelGGL(csc_fill_packed_kernel, dim3(nblk(n)), dim3(TB), 0, s, (long)n, vs, packed, L->rowidx,
                                    L->csr_pos, L->valT, L->velT);
             } else {
@@ -721,9 +756,6 @@ int topo_finalize(sl_layer *L, hipStream_t s, bool packed_ready)
         L->bwd.n_rows = n_in; L->bwd.ptr = L->colptr; L->bwd.idx = L->rowidx;
         launch_max_len(L, L->bwd, SMALL_MAXLEN_B, s);
     }
-    if (!L->has_csc && short_rows(L) && !packed_ready && n > 0)
-        hipLaunchKernelGGL(pack_rows_kernel, dim3(nblk(n_out)), dim3(TB), 0, s, n_out, L->rowptr, L->val, L->vel, L->rowid,
-                           (RowValVel *)nullptr);
     SL_HIP(L, hipGetLastError());
     int maxlen[2] = {0, 0};
     int rc = read_back(L, maxlen, at<int>(L, L->cp.small) + SMALL_MAXLEN_F, sizeof(int) * (L->has_csc ? 2 : 1), s);
@@ -836,27 +868,23 @@ static int rebuild(sl_layer *L, long ns, long k, uint32_t generation, hipStream_
     const uint64_t *new_p = at<uint64_t>(L, L->cp.new_p);
     hipLaunchKernelGGL(merge_rowptr_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, n_out, n_in, rowptr_s, new_p, k,
                        L->rowptr);
-    bool packed = false;
-    if (short_rows(L)) {
-        packed = true;      // row ids (and, with a transposed view, the packed copy) are written by the merge itself
-        RowValVel *pk = L->has_csc ? at<RowValVel>(L, L->cp.packed) : (RowValVel *)nullptr;
-        if (ns > 0)
-            hipLaunchKernelGGL(merge_survivor_rows_kernel, dim3(nblk(ns)), dim3(TB), 0, s, ns, n_in, rowptr_s,
-                               at<int>(L, L->cp.s_row), s_col, s_val, s_vel, new_p, L->rowptr, L->colidx, L->val, L->vel,
-                               L->rowid, pk);
-        if (k > 0)
-            hipLaunchKernelGGL(merge_new_rows_kernel, dim3(nblk(k)), dim3(TB), 0, s, k, n_in, rowptr_s, s_col, new_p,
-                               make_rng(L, generation), L->cfg.init_limit, L->colidx, L->val, L->vel, L->rowid, pk);
-    } else {
-        if (ns > 0)
-            hipLaunchKernelGGL(merge_survivor_kernel, dim3(nblk(ns)), dim3(TB), 0, s, ns, n_out, n_in, rowptr_s, s_col,
-                               s_val, s_vel, new_p, k, L->colidx, L->val, L->vel);
-        if (k > 0)
-            hipLaunchKernelGGL(merge_new_kernel, dim3(nblk(k)), dim3(TB), 0, s, k, n_in, rowptr_s, s_col, new_p,
-                               make_rng(L, generation), L->cfg.init_limit, L->colidx, L->val, L->vel);
+    const long n = ns + k;
+    if (n > 0) {
+        const long n_tiles = (n + MERGE_TILE - 1) / MERGE_TILE;
+        int2 *tile_rows = at<int2>(L, L->cp.f0);      // the sampler is done with its flag arrays
+        hipLaunchKernelGGL(merge_tile_rows_kernel, dim3(nblk(n_tiles)), dim3(TB), 0, s, n_tiles, n_out, L->rowptr, n, tile_rows);
+        const Rng rng = make_rng(L, generation);
+        if (L->has_csc)
+            hipLaunchKernelGGL(merge_rows_kernel<true>, dim3((unsigned)n_tiles), dim3(TB), 0, s, n, n_in, tile_rows, rowptr_s,
+                               L->rowptr, s_col, s_val, s_vel, new_p, rng, L->cfg.init_limit, L->colidx, L->val, L->vel,
+                               at<RowValVel>(L, L->cp.packed), at<uint32_t>(L, L->cp.keyA), at<uint32_t>(L, L->cp.payA));
+        else
+            hipLaunchKernelGGL(merge_rows_kernel<false>, dim3((unsigned)n_tiles), dim3(TB), 0, s, n, n_in, tile_rows, rowptr_s,
+                               L->rowptr, s_col, s_val, s_vel, new_p, rng, L->cfg.init_limit, L->colidx, L->val, L->vel,
+                               (RowValVel *)nullptr, (uint32_t *)nullptr, (uint32_t *)nullptr);
     }
     SL_HIP(L, hipGetLastError());
-    return topo_finalize(L, s, packed);
+    return topo_finalize(L, s, true);
 }
 
 // RetainValidUpdates (Algorithm 1): the gradient of master entry t is the old gradient of the same
@@ -916,8 +944,8 @@ int topo_importance_prune(sl_layer *L, float threshold, int64_t *removed, hipStr
     rc = read_back(L, &kept, kscan + n, sizeof(uint32_t), s);
     if (rc) return rc;
     if ((long)kept == n) return SL_OK;
-    hipLaunchKernelGGL(compact_kernel, dim3(nblk(n)), dim3(TB), 0, s, n, keep, kscan, L->colidx, L->val, L->vel,
-                       (const int *)nullptr, s_col, s_val, s_vel, (int *)nullptr);
+    hipLaunchKernelGGL(compact_kernel, dim3(nblk(n)), dim3(TB), 0, s, n, keep, kscan, L->colidx, L->val, L->vel, s_col,
+                       s_val, s_vel);
     hipLaunchKernelGGL(survivor_rowptr_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, n_out, L->rowptr, kscan, rowptr_s);
     hipLaunchKernelGGL(copy_back_kernel, dim3(nblk(kept)), dim3(TB), 0, s, (long)kept, s_col, s_val, s_vel, L->colidx,
                        L->val, L->vel);
@@ -1054,8 +1082,7 @@ int topo_evolve(sl_layer *L, double zeta, uint32_t generation, hipStream_t s)
     hipLaunchKernelGGL(keep_flag_kernel, dim3(nblk(n + 1)), dim3(TB), 0, s, L->val, n, mode, L->sel, trank, keep);
     SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, keep, kscan, (size_t)n + 1, s));
     hipLaunchKernelGGL(compact_kernel, dim3(nblk(n)), dim3(TB), 0, s, n, keep, kscan, L->colidx, L->val, L->vel,
-                       short_rows(L) ? L->rowid : (const int *)nullptr, at<int>(L, L->cp.s_col), at<float>(L, L->cp.s_val),
-                       at<float>(L, L->cp.s_vel), at<int>(L, L->cp.s_row));
+                       at<int>(L, L->cp.s_col), at<float>(L, L->cp.s_val), at<float>(L, L->cp.s_vel));
     hipLaunchKernelGGL(survivor_rowptr_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, n_out, L->rowptr, kscan,
                        at<int>(L, L->cp.rowptr_s));
     // the survivor count is checked at the sampler's read-back

@@ -1093,6 +1093,41 @@ def test_training_step_with_and_without_fused_update(gpu):
                                   v.view(np.uint32) if v.dtype == np.float32 else v)
 
 
+def test_layers_evolve_together_as_they_do_alone(gpu):
+    """sparse_layers_evolve (every layer on a stream and host thread of its own, the default of SparseMLP.evolve)
+    against one sparse_layer_evolve call per layer: identical bits in every array of every layer over three trained
+    generations and both prune modes; layers that share a scratch buffer are turned away."""
+    import ctypes as C
+    import torch
+    for name, mode in (("set_mlp_madelon", 0), ("set_mlp_fmnist", 1)):
+        w = wl.WORKLOADS[name]
+        X, y = wl.dataset(w, 3 * w.batch)
+        blocks = dev(torch, wl.to_batch_blocks(X, w.batch))
+        yd = dev(torch, y)
+        states = []
+        for shared in (True, False):
+            net = gpu.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=w.batch,
+                                prune_mode=mode, shared_scratch=shared)
+            for gen in (1, 2, 3):
+                for k in range(3):
+                    net.train_step(blocks[k], yd[k * w.batch:(k + 1) * w.batch], w.batch)
+                net.evolve(0.3, gen)
+            states.append([L.export_csr() for L in net.layers])
+            if shared:   # one buffer under all layers: the concurrent form must refuse
+                streams = (C.c_void_p * len(net.layers))(*[None] * len(net.layers))
+                rc = gpu.lib().sparse_layers_evolve(net._handles, len(net.layers), 0.3, 9, streams)
+                assert rc == gpu.SL_EINVAL
+                assert "scratch" in gpu.lib().sparse_layer_last_error(net.layers[1].handle).decode()
+                after = [L.export_csr() for L in net.layers]
+                for la, lb in zip(states[0], after):
+                    assert all(np.array_equal(u, v) for u, v in zip(la, lb))
+            net.close()
+        for la, lb in zip(*states):
+            for u, v in zip(la, lb):
+                assert np.array_equal(u.view(np.uint32) if u.dtype == np.float32 else u,
+                                      v.view(np.uint32) if v.dtype == np.float32 else v)
+
+
 # ------------------------------------------------------------------------------------------ sampler window
 @pytest.mark.parametrize("n_in,n_out,nnz", [(500, 400, 9000), (100000, 70000, 1700000)])
 def test_sampler_window_growth_and_failure(gpu, oracle, n_in, n_out, nnz):

@@ -66,6 +66,9 @@ def test_query_sizes_and_argument_errors(lib):
     assert lib.sparse_layer_infer_static(None, None, 0, 0, None, 0, None) == binding.SL_EINVAL
     assert lib.sparse_layer_set_fused_update(None, 1) == binding.SL_EINVAL
     assert lib.sparse_layer_set_sampler_window(None, 0, 0) == binding.SL_EINVAL
+    assert lib.sparse_layers_evolve(None, 1, 0.3, 1, None) == binding.SL_EINVAL
+    none = (C.c_void_p * 2)(None, None)
+    assert lib.sparse_layers_evolve(none, 2, 0.3, 1, none) == binding.SL_EINVAL
     assert lib.sparse_loss_softmax_ce(None, 0, None, 1, 2, None, 0, None, None) == binding.SL_EINVAL
     out = C.c_void_p(None)
     assert lib.sparse_layer_init(C.byref(cfg), None, 0, None, 0, None, C.byref(out)) == binding.SL_EINVAL
