@@ -989,7 +989,7 @@ static void launch_bwd_kernel_u(int G, int U, int B, int nv, BwdArgs b, hipStrea
 {
     b.tile0 = 0;
     b.tile1 = (B + 4 * G - 1) / (4 * G);
-    if (B > 256) {
+    if (B > 256 && G == 64) {
         // One launch per pair of tiles: all groups then gather from the same 512 columns at a time (measured
         // 15 % faster at 1024 columns), and the stream order makes a later pair add to the gradient entries
         // that the earlier pair stored.  Very short rows (chunks of 2) walk all pairs in one launch instead:
@@ -1061,6 +1061,16 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
         b.vptr = m.vptr; b.v2row = m.v2row; b.nv = m.nv; b.idx = m.idx; b.w = L->valT;
         b.held = x; b.ldh = (int)ldx; b.gath = L->dz; b.ldga = L->ldz;
         if (m.split) b.part = (float *)(L->scratch + L->cp.partial);
+        // Wide batches over columns of 7 to 16 connections: per-row work (row pointers, held row, epilogue) weighs
+        // more against so few gathers of 1 KB, and one launch of 32-lane groups per 128-column slice is faster than
+        // the 64-lane pair walk (262 144 x 262 144 layer with 8 connections per column, B = 512: 0.90 -> 0.77 ms);
+        // from about 32 connections per column on the pair walk wins.
+        int Gb = G;
+        if (B > 256 && U == 8 && L->nnz <= 16 * (int64_t)m.nv) {
+            Gb = 32;
+            b.slice_tiles = 1;
+            b.n_tiles = (B + 127) / 128;
+        }
         sl_layer *P = gx ? nullptr : L->producer;
         if (P) {   // hand dz straight to the layer that produced x
             b.epi = dz_epilogue(P, B);
@@ -1071,9 +1081,9 @@ int launch_backward(sl_layer *L, const float *x, int64_t ldx, const float *ga, i
         }
         {
             ProfScope ps(L, K_BWD_FUSED, s);
-            launch_bwd_kernel<true>(G, U, B, m.nv, b, s);
+            launch_bwd_kernel<true>(Gb, U, B, m.nv, b, s);
         }
-        if (m.split) launch_fix(L, m, b.epi, G, K_BWD_FIX, s);
+        if (m.split) launch_fix(L, m, b.epi, Gb, K_BWD_FIX, s);
         if (P) P->dz_ready = B;
     } else {
         const SegMat &m = L->fwd;

@@ -80,7 +80,10 @@ def test_init_topology_bit_exact(gpu, oracle, n_in, n_out, nnz):
     (200, 150, 3000, 200, 256, 1, 1, True),       # G = 64 path
     (200, 150, 3000, 300, 512, 1, 0, True),       # two batch tiles of 256 columns, ragged tail
     (200, 150, 3000, 299, 512, 1, 0, False),      # SDDMM-only path, tiles + ragged
-    (200, 150, 3000, 600, 1024, 1, 0, True),      # three batch tiles: a pair, then a single one
+    (200, 150, 3000, 600, 1024, 1, 0, True),      # columns of 15 connections: one launch per 128-column slice, five of them
+    (300, 250, 3000, 1021, 1024, 1, 0, True),     # the same walk, eight slices, ragged tail
+    (200, 150, 6000, 600, 1024, 1, 0, True),      # columns of 30: three batch tiles of 256, a pair, then a single one
+    (200, 150, 6000, 1021, 1024, 1, 1, True),     # two pairs, ragged tail
     (200, 150, 3000, 1021, 1024, 1, 1, False),    # four batch tiles, ragged, SDDMM only
     (6, 2000, 12000, 300, 512, 1, 0, True),       # split CSC side with two batch tiles
     (400, 2, 800, 128, 128, 0, 0, True),          # dense output layer: long rows are split
@@ -1019,6 +1022,7 @@ def test_training_learns_and_is_reproducible(gpu):
     (500, 400, 9000, 128, 128, True), (500, 400, 9000, 128, 128, False),      # CSC-ordered and CSR-ordered (first layer)
     (300, 700, 6000, 31, 32, True), (256, 300, 4000, 64, 64, False),          # groups of 8 and 16 lanes, ragged
     (200, 150, 3000, 600, 1024, True), (200, 150, 3000, 1021, 1024, False),   # batch tiles: the update waits for the last one
+    (200, 150, 6000, 600, 1024, True),                                        # longer columns: the pair walk
     (6, 2000, 12000, 300, 512, True), (400, 2, 800, 128, 128, True),          # split columns / split rows
     (1500, 2500, 5000, 1000, 1024, True),                                     # very short rows: all tile pairs in one launch
     (3000, 5000, 37, 128, 128, True)])
