@@ -153,6 +153,121 @@ static void run_walk()
     CHECK(hipFree(didx));
 }
 
+// The same walk in lock-step: the workgroups of one XCD (read from the XCC_ID hardware register) wait, before they start
+// column block k, until all of them have finished block k - slack, so that the XCD's L2 holds the blocks being read.
+// Every wait is bounded (spin_limit polls, then the workgroup goes on and the launch counts a time-out), every workgroup
+// of the grid is resident (1024 or 2048 workgroups of 256 threads on 256 CUs), so every wave reaches the end.
+__device__ __forceinline__ unsigned ld_acquire(const unsigned *p) { return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT); }
+
+__global__ __launch_bounds__(256) void walk_sync(const float *x, const int *idx, int ngroups, int steps, int per_block, int n_visits,
+                                                 int slack, int spin_limit, unsigned *done /* [8][n_visits] */,
+                                                 unsigned *xcd_groups /* [8] workgroups per XCD, [8] = all arrived, [9] = time-outs */,
+                                                 float *out)
+{
+    __shared__ unsigned my_total;
+    const int xcc = (int)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7u);   // HW_REG_XCC_ID, bits 3:0
+    if (threadIdx.x == 0) {
+        // sign in, then wait (bounded) until the whole grid has: after that the per-XCD head counts are final
+        __hip_atomic_fetch_add(&xcd_groups[xcc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(&xcd_groups[8], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        int spins = 0;
+        while (ld_acquire(&xcd_groups[8]) < gridDim.x && ++spins < 100 * spin_limit) __builtin_amdgcn_s_sleep(2);
+        my_total = ld_acquire(&xcd_groups[xcc]);
+    }
+    __syncthreads();
+    const unsigned mates = my_total;
+    const int g = blockIdx.x * 8 + threadIdx.x / 32;
+    const int lane = threadIdx.x % 32;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int *my = idx + (long)min(g, ngroups - 1) * steps * 8;
+    for (int kb = 0; kb < n_visits; ++kb) {
+        if (kb >= slack) {
+            if (threadIdx.x == 0) {
+                int spins = 0;
+                while (ld_acquire(&done[xcc * n_visits + kb - slack]) < mates && ++spins < spin_limit) __builtin_amdgcn_s_sleep(1);
+                if (spins >= spin_limit) __hip_atomic_fetch_add(&xcd_groups[9], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __syncthreads();
+        }
+        for (int s = kb * per_block; s < (kb + 1) * per_block; ++s) {
+            int c[8];
+            float4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) c[u] = my[s * 8 + u];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *(const float4 *)(x + (long)c[u] * 128 + lane * 4);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+        }
+        __syncthreads();   // the loads above have returned (their values were added) in every wave of the workgroup
+        if (threadIdx.x == 0) __hip_atomic_fetch_add(&done[xcc * n_visits + kb], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (acc.x == 12345.f) out[g] = acc.y + acc.z + acc.w;   // never true: keeps the loads alive
+}
+
+static void run_walk_sync()
+{
+    const int n = 262144;
+    const long total = 33554432;   // gathers per launch
+    float *x, *out;
+    int *didx;
+    unsigned *done, *xg;
+    CHECK(hipMalloc(&x, (size_t)n * 512));
+    CHECK(hipMemset(x, 0, (size_t)n * 512));
+    CHECK(hipMalloc(&didx, total * 4));
+    CHECK(hipMalloc(&out, 16384 * 4));
+    CHECK(hipMalloc(&done, 8 * 4096 * 4));
+    CHECK(hipMalloc(&xg, 16 * 4));
+    printf("# blocked walk in lock-step per XCD (bounded waits; slack = column blocks a workgroup may run ahead of the slowest of its XCD)\n");
+    std::vector<int> h((size_t)total);
+    for (int ngroups : {16384, 8192})
+        for (int nb : {32, 64, 128})
+            for (int slack : {1, 2}) {
+                const int steps = (int)(total / 8 / ngroups);
+                const int passes = 4;
+                const int per_block = steps / (passes * nb);
+                if (per_block < 1) continue;
+                const int n_visits = passes * nb;
+                const int bsize = n / nb;
+                std::mt19937 rng(7);
+                for (int g = 0; g < ngroups; ++g)
+                    for (int s = 0; s < steps; ++s) {
+                        const int blk = (s / per_block) % nb;
+                        for (int u = 0; u < 8; ++u) h[((size_t)g * steps + s) * 8 + u] = blk * bsize + (int)(rng() % bsize);
+                    }
+                CHECK(hipMemcpy(didx, h.data(), total * 4, hipMemcpyHostToDevice));
+                hipEvent_t a, b;
+                CHECK(hipEventCreate(&a));
+                CHECK(hipEventCreate(&b));
+                float best = 1e9f;
+                unsigned info[16] = {0};
+                for (int rep = 0; rep < 4; ++rep) {
+                    CHECK(hipMemset(done, 0, 8 * 4096 * 4));
+                    CHECK(hipMemset(xg, 0, 16 * 4));
+                    CHECK(hipEventRecord(a));
+                    hipLaunchKernelGGL(walk_sync, dim3(ngroups / 8), dim3(256), 0, 0, x, didx, ngroups, steps, per_block, n_visits, slack,
+                                       2000, done, xg, out);
+                    CHECK(hipEventRecord(b));
+                    CHECK(hipEventSynchronize(b));
+                    float ms;
+                    CHECK(hipEventElapsedTime(&ms, a, b));
+                    if (rep > 0 && ms < best) best = ms;
+                    CHECK(hipMemcpy(info, xg, sizeof(info), hipMemcpyDeviceToHost));
+                }
+                printf("%5d groups, %3d column blocks of %5.2f MB, slack %d: %.3f ms, %.2f TB/s gathered; workgroups per XCD %u %u %u %u %u %u %u %u, waits timed out %u\n",
+                       ngroups, nb, bsize * 512.0 / 1e6, slack, best, total * 512.0 / best / 1e9, info[0], info[1], info[2], info[3], info[4],
+                       info[5], info[6], info[7], info[9]);
+                fflush(stdout);
+                CHECK(hipEventDestroy(a));
+                CHECK(hipEventDestroy(b));
+            }
+    CHECK(hipFree(x));
+    CHECK(hipFree(out));
+    CHECK(hipFree(didx));
+    CHECK(hipFree(done));
+    CHECK(hipFree(xg));
+}
+
 // Third question: what does the mix of the sparsest sweep layer (epsilon = 1: two random 512-byte row gathers per
 // 512-byte output row written, i.e. a third of the traffic in writes) reach when nothing else is done?  Each group
 // produces four consecutive output rows (as the span forward kernel does), each the sum of `fan` gathered rows.
@@ -221,6 +336,7 @@ int main()
     run<8>({65536L, 262144L, 1048576L}, total / 4);
     run<64>({65536L, 262144L, 1048576L}, total);
     run_walk();
+    run_walk_sync();
     run_gather_write();
     return 0;
 }
