@@ -1165,6 +1165,31 @@ def test_sampler_window_growth_and_failure(gpu, oracle, n_in, n_out, nnz):
     G.close()
 
 
+def test_one_layer_failing_while_the_layers_evolve_together(gpu):
+    """sparse_layers_evolve when one layer's cycle fails (its sampler window may not grow): the call reports that
+    layer's error, the layer is exactly as it was, and the other layers have completed their own cycle (same bits as
+    a network in which nothing failed)."""
+    w = wl.WORKLOADS["set_mlp_madelon"]
+    nets = [gpu.SparseMLP(w.layers, alpha=w.alpha, lr=w.lr, momentum=w.momentum, seed=w.seed, max_batch=w.batch)
+            for _ in range(2)]
+    before = nets[0].layers[1].export_csr()
+    nets[0].layers[1].set_sampler_window(16, 64)
+    with pytest.raises(gpu.SparseSetError) as e:
+        nets[0].evolve(0.3, 1)
+    assert e.value.code == gpu.SL_ESTATE and "sampler" in str(e.value)
+    nets[1].evolve(0.3, 1)
+    same = lambda a, b: all(np.array_equal(u.view(np.uint32) if u.dtype == np.float32 else u,
+                                           v.view(np.uint32) if v.dtype == np.float32 else v) for u, v in zip(a, b))
+    assert same(before, nets[0].layers[1].export_csr())
+    for li in (0, 2, 3):
+        assert same(nets[0].layers[li].export_csr(), nets[1].layers[li].export_csr())
+    nets[0].layers[1].set_sampler_window(0, 0)          # and the layer that failed still evolves afterwards
+    nets[0].layers[1].evolve(0.3, 1)
+    assert same(nets[0].layers[1].export_csr(), nets[1].layers[1].export_csr())
+    for net in nets:
+        net.close()
+
+
 def test_softmax_cross_entropy_label_out_of_range(gpu):
     """A label outside [0, C) (padding, an uninitialised buffer) is never used as an index: the sample adds nothing
     to the loss and its gradient is softmax(z) / B; the labelled samples are untouched by it."""
