@@ -151,25 +151,58 @@ __global__ void select_setup_kernel(SelState *st, uint32_t k0, uint32_t k1)
     s.hist[threadIdx.x] = 0;
 }
 
-__global__ void select_hist_kernel(const float *val, long n, int mode, int shift, SelState *st)
+// Few, large workgroups: every workgroup ends with up to 512 atomic additions to the same 512 global counters, and
+// those serialise per counter (with 2048 workgroups they took three quarters of the pass).
+constexpr int HIST_TB = 1024, HIST_BLOCKS = 512;
+__global__ __launch_bounds__(HIST_TB) void select_hist_kernel(const float *val, long n, int mode, int shift, SelState *st)
 {
     __shared__ uint32_t h[2][256];
-    h[0][threadIdx.x] = 0;
-    h[1][threadIdx.x] = 0;
+    if (threadIdx.x < 256) {
+        h[0][threadIdx.x] = 0;
+        h[1][threadIdx.x] = 0;
+    }
     __syncthreads();
     const uint32_t act0 = st[0].active, act1 = st[1].active;
     const uint32_t pre0 = st[0].prefix, pre1 = st[1].prefix;
-    for (long p = (long)blockIdx.x * TB + threadIdx.x; p < n; p += (long)gridDim.x * TB) {
-        const float w = val[p];
+    // Neighbouring weights mostly share their leading digit (the first pass sees two or three exponent values in
+    // all), and additions of a whole wavefront to one LDS counter serialise: a lane adds a run of equal digits at once.
+    int run_bin = -1;
+    uint32_t run_len = 0;
+    auto flush = [&]() {
+        if (run_len) atomicAdd(&h[run_bin >> 8][run_bin & 255], run_len);
+        run_len = 0;
+    };
+    auto count = [&](float w) {
         const int c = weight_class(w, mode);
         const uint32_t mag = __float_as_uint(w) & 0x7FFFFFFFu;
         const uint32_t act = c ? act1 : act0, pre = c ? pre1 : pre0;
         const bool in = act && (shift == 24 || (mag >> (shift + 8)) == pre);
-        if (in) atomicAdd(&h[c][(mag >> shift) & 255u], 1u);
+        if (!in) return;
+        const int bin = (c << 8) | (int)((mag >> shift) & 255u);
+        if (bin != run_bin) { flush(); run_bin = bin; }
+        ++run_len;
+    };
+    // eight weights per lane and trip (two 16-byte loads issued before the first is used)
+    const long n8 = n / 8;
+    const float4 *v4 = (const float4 *)val;
+    for (long q = (long)blockIdx.x * HIST_TB + threadIdx.x; q < n8; q += (long)gridDim.x * HIST_TB) {
+        const float4 a = v4[2 * q], b = v4[2 * q + 1];
+        count(a.x); count(a.y); count(a.z); count(a.w);
+        count(b.x); count(b.y); count(b.z); count(b.w);
     }
+    for (long p = n8 * 8 + (long)blockIdx.x * HIST_TB + threadIdx.x; p < n; p += (long)gridDim.x * HIST_TB) count(val[p]);
+    flush();
     __syncthreads();
-    if (h[0][threadIdx.x]) atomicAdd(&st[0].hist[threadIdx.x], h[0][threadIdx.x]);
-    if (h[1][threadIdx.x]) atomicAdd(&st[1].hist[threadIdx.x], h[1][threadIdx.x]);
+    if (threadIdx.x < 256) {
+        if (h[0][threadIdx.x]) atomicAdd(&st[0].hist[threadIdx.x], h[0][threadIdx.x]);
+        if (h[1][threadIdx.x]) atomicAdd(&st[1].hist[threadIdx.x], h[1][threadIdx.x]);
+    }
+}
+
+static void launch_select_hist(const float *val, long n, int mode, int shift, SelState *st, hipStream_t s)
+{
+    const long blocks = std::max<long>(1, std::min<long>(HIST_BLOCKS, (n + 8 * HIST_TB - 1) / (8 * HIST_TB)));
+    hipLaunchKernelGGL(select_hist_kernel, dim3((unsigned)blocks), dim3(HIST_TB), 0, s, val, n, mode, shift, st);
 }
 
 // picks the digit that contains the krem-th smallest remaining key; on the last pass the prefix is
@@ -1013,7 +1046,7 @@ int topo_average(sl_layer *D, sl_layer *const *reps, int K, char *scr, size_t sc
     hipLaunchKernelGGL(select_setup_kernel, dim3(2), dim3(256), 0, s, D->sel, (uint32_t)k_remove, 0u);
     if (k_remove > 0)
         for (int shift = 24; shift >= 0; shift -= 8) {
-            hipLaunchKernelGGL(select_hist_kernel, dim3(std::min(2048u, nblk(U))), dim3(TB), 0, s, uval, U, 0, shift, D->sel);
+            launch_select_hist(uval, U, 0, shift, D->sel, s);
             hipLaunchKernelGGL(select_pick_kernel, dim3(2), dim3(256), 0, s, D->sel, shift == 0 ? 1 : 0);
         }
     hipLaunchKernelGGL(tie_flag_kernel, dim3(nblk(U + 1)), dim3(TB), 0, s, uval, U, 0, D->sel, tie);
@@ -1055,7 +1088,7 @@ int topo_evolve(sl_layer *L, double zeta, uint32_t generation, hipStream_t s)
     if (mode == 1) {
         uint32_t *small = at<uint32_t>(L, L->cp.small) + SMALL_CLASS;
         hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(TB), 0, s, 1L, small);
-        if (n > 0) hipLaunchKernelGGL(class_count_kernel, dim3(std::min(1024u, nblk(n))), dim3(TB), 0, s, L->val, n, small);
+        if (n > 0) hipLaunchKernelGGL(class_count_kernel, dim3(std::min(256u, nblk(n))), dim3(TB), 0, s, L->val, n, small);
         uint32_t neg = 0;
         rc = read_back(L, &neg, small, sizeof(uint32_t), s);
         if (rc) return rc;
@@ -1071,7 +1104,7 @@ int topo_evolve(sl_layer *L, double zeta, uint32_t generation, hipStream_t s)
     if (k == 0) return SL_OK;
     hipLaunchKernelGGL(select_setup_kernel, dim3(2), dim3(256), 0, s, L->sel, (uint32_t)kc[0], (uint32_t)kc[1]);
     for (int shift = 24; shift >= 0; shift -= 8) {
-        hipLaunchKernelGGL(select_hist_kernel, dim3(std::min(2048u, nblk(n))), dim3(TB), 0, s, L->val, n, mode, shift, L->sel);
+        launch_select_hist(L->val, n, mode, shift, L->sel, s);
         hipLaunchKernelGGL(select_pick_kernel, dim3(2), dim3(256), 0, s, L->sel, shift == 0 ? 1 : 0);
     }
     uint64_t *tie = at<uint64_t>(L, L->cp.tie64), *trank = at<uint64_t>(L, L->cp.trank);
