@@ -210,12 +210,15 @@ static void launch_select_hist(const float *val, long n, int mode, int shift, Se
 __global__ void select_pick_kernel(SelState *st, int last)
 {
     SelState &s = st[blockIdx.x];
+    __shared__ uint32_t h[256];               // one parallel fetch instead of 256 dependent global loads
+    h[threadIdx.x] = s.hist[threadIdx.x];
+    __syncthreads();
     if (threadIdx.x == 0 && s.active) {
         uint32_t cum = 0;
         int d = 0;
         for (; d < 255; ++d) {
-            if (cum + s.hist[d] >= s.krem) break;
-            cum += s.hist[d];
+            if (cum + h[d] >= s.krem) break;
+            cum += h[d];
         }
         s.krem -= cum;
         s.prefix = (s.prefix << 8) | (uint32_t)d;
@@ -260,6 +263,168 @@ __global__ void keep_flag_kernel(const float *val, long n, int mode, const SelSt
         k = gone ? 0u : 1u;
     }
     keep[p] = k;
+}
+
+// The same decisions for the prune / regrow cycle without device-wide scans over the connections: every workgroup of
+// PRUNE_TILE consecutive entries (four per thread) counts its ties (tie_count_kernel), a scan over the per-workgroup
+// counts gives each workgroup the number of ties before it, a second pass counts the survivors per workgroup
+// (keep_count_kernel), and after the scan of those counts the compaction (compact_block_kernel) recomputes the
+// decision and places the survivors.  Ranks and slots inside a workgroup come from a wavefront prefix sum of the
+// threads' counts.  Entry n is a sentinel that is never kept.
+constexpr int PRUNE_PER = 4, PRUNE_TILE = PRUNE_PER * TB;
+
+__device__ __forceinline__ uint32_t block_excl_sum(uint32_t v, uint32_t *wave_tot, uint32_t &block_total)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();                       // wave_tot may still be read from an earlier call
+    if (lane == 63) wave_tot[wv] = inc;
+    __syncthreads();
+    uint32_t off = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < TB / 64; ++w) {
+        const uint32_t c = wave_tot[w];
+        if (w < wv) off += c;
+        tot += c;
+    }
+    block_total = tot;
+    return off + inc - v;
+}
+
+// the thread's four entries p0 .. p0+3 (those below n): magnitude, class, whether the class prunes at all, tie with its threshold
+struct Quad {
+    float w[PRUNE_PER];
+    uint32_t mag[PRUNE_PER];
+    int c[PRUNE_PER];
+    bool active[PRUNE_PER], tie[PRUNE_PER];
+};
+__device__ __forceinline__ Quad quad_of(const float *val, long p0, long n, int mode, const SelState *st)
+{
+    Quad q;
+    if (p0 + PRUNE_PER <= n) {
+        const float4 v = *(const float4 *)(val + p0);
+        q.w[0] = v.x; q.w[1] = v.y; q.w[2] = v.z; q.w[3] = v.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < PRUNE_PER; ++e) q.w[e] = p0 + e < n ? val[p0 + e] : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < PRUNE_PER; ++e) {
+        const bool in = p0 + e < n;
+        q.c[e] = weight_class(q.w[e], mode);
+        q.mag[e] = __float_as_uint(q.w[e]) & 0x7FFFFFFFu;
+        q.active[e] = in && st[q.c[e]].active != 0;
+        q.tie[e] = q.active[e] && q.mag[e] == st[q.c[e]].thresh;
+    }
+    return q;
+}
+__device__ __forceinline__ void tie_counts(const Quad &q, uint32_t &n0, uint32_t &n1)
+{
+    n0 = 0; n1 = 0;
+#pragma unroll
+    for (int e = 0; e < PRUNE_PER; ++e) {
+        n0 += (q.tie[e] && q.c[e] == 0) ? 1u : 0u;
+        n1 += (q.tie[e] && q.c[e] == 1) ? 1u : 0u;
+    }
+}
+
+__global__ __launch_bounds__(TB) void tie_count_kernel(const float *val, long n, int mode, const SelState *st, uint64_t *blk_tie)
+{
+    __shared__ uint32_t wt[TB / 64];
+    const long p0 = ((long)blockIdx.x * TB + threadIdx.x) * PRUNE_PER;
+    const Quad q = quad_of(val, p0, n, mode, st);
+    uint32_t n0, n1, t0, t1;
+    tie_counts(q, n0, n1);
+    block_excl_sum(n0, wt, t0);
+    block_excl_sum(n1, wt, t1);
+    if (threadIdx.x == 0) blk_tie[blockIdx.x] = ((uint64_t)t1 << 32) | t0;
+}
+
+// keep = not among the removed ones: magnitude below the threshold, or equal to it and among the first `need` such
+// entries in CSR order (= smallest flat positions).  Returns the four decisions as bits.
+__device__ __forceinline__ uint32_t keep_of(const Quad &q, long p0, long n, const SelState *st, uint64_t ties_before_block,
+                                            uint32_t *wt)
+{
+    uint32_t n0, n1, tot;
+    tie_counts(q, n0, n1);
+    uint32_t r0 = (uint32_t)ties_before_block + block_excl_sum(n0, wt, tot);
+    uint32_t r1 = (uint32_t)(ties_before_block >> 32) + block_excl_sum(n1, wt, tot);
+    uint32_t bits = 0;
+#pragma unroll
+    for (int e = 0; e < PRUNE_PER; ++e) {
+        bool keep = p0 + e < n;
+        if (q.active[e]) {
+            const uint32_t rank = q.c[e] ? r1 : r0;
+            if (q.mag[e] < st[q.c[e]].thresh || (q.tie[e] && rank < st[q.c[e]].need)) keep = false;
+            if (q.tie[e]) { if (q.c[e]) ++r1; else ++r0; }
+        }
+        bits |= keep ? (1u << e) : 0u;
+    }
+    return bits;
+}
+
+__global__ __launch_bounds__(TB) void keep_count_kernel(const float *val, long n, int mode, const SelState *st,
+                                                        const uint64_t *blk_tie_off, uint32_t *blk_keep)
+{
+    __shared__ uint32_t wt[TB / 64];
+    const long p0 = ((long)blockIdx.x * TB + threadIdx.x) * PRUNE_PER;
+    const Quad q = quad_of(val, p0, n, mode, st);
+    const uint32_t bits = keep_of(q, p0, n, st, blk_tie_off[blockIdx.x], wt);
+    uint32_t kept;
+    block_excl_sum((uint32_t)__popc(bits), wt, kept);
+    if (threadIdx.x == 0) blk_keep[blockIdx.x] = kept;
+}
+
+// kscan[p] = survivors before entry p (for p = 0 .. n; the row pointers of the survivors are read from it)
+__global__ __launch_bounds__(TB) void compact_block_kernel(const float *val, long n, int mode, const SelState *st,
+                                                           const uint64_t *blk_tie_off, const uint32_t *blk_keep_off,
+                                                           const int *col, const float *vel, uint32_t *kscan, int *s_col,
+                                                           float *s_val, float *s_vel)
+{
+    __shared__ uint32_t wt[TB / 64];
+    const long p0 = ((long)blockIdx.x * TB + threadIdx.x) * PRUNE_PER;
+    const Quad q = quad_of(val, p0, n, mode, st);
+    const uint32_t bits = keep_of(q, p0, n, st, blk_tie_off[blockIdx.x], wt);
+    uint32_t kept;
+    uint32_t d = blk_keep_off[blockIdx.x] + block_excl_sum((uint32_t)__popc(bits), wt, kept);
+    if (p0 > n) return;
+    int ci[PRUNE_PER];
+    float ve[PRUNE_PER];
+    if (p0 + PRUNE_PER <= n) {
+        const int4 c4 = *(const int4 *)(col + p0);
+        const float4 v4 = *(const float4 *)(vel + p0);
+        ci[0] = c4.x; ci[1] = c4.y; ci[2] = c4.z; ci[3] = c4.w;
+        ve[0] = v4.x; ve[1] = v4.y; ve[2] = v4.z; ve[3] = v4.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < PRUNE_PER; ++e) {
+            ci[e] = p0 + e < n ? col[p0 + e] : 0;
+            ve[e] = p0 + e < n ? vel[p0 + e] : 0.f;
+        }
+    }
+    uint32_t ks[PRUNE_PER];
+#pragma unroll
+    for (int e = 0; e < PRUNE_PER; ++e) {
+        ks[e] = d;
+        if (bits & (1u << e)) {
+            s_col[d] = ci[e];
+            s_val[d] = q.w[e];
+            s_vel[d] = ve[e];
+            ++d;
+        }
+    }
+    if (p0 + PRUNE_PER <= n + 1) {
+        *(uint4 *)(kscan + p0) = make_uint4(ks[0], ks[1], ks[2], ks[3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < PRUNE_PER; ++e)
+            if (p0 + e <= n) kscan[p0 + e] = ks[e];
+    }
 }
 
 __global__ void compact_kernel(long n, const uint32_t *keep, const uint32_t *kscan, const int *col, const float *val,
@@ -1107,15 +1272,17 @@ int topo_evolve(sl_layer *L, double zeta, uint32_t generation, hipStream_t s)
         launch_select_hist(L->val, n, mode, shift, L->sel, s);
         hipLaunchKernelGGL(select_pick_kernel, dim3(2), dim3(256), 0, s, L->sel, shift == 0 ? 1 : 0);
     }
-    uint64_t *tie = at<uint64_t>(L, L->cp.tie64), *trank = at<uint64_t>(L, L->cp.trank);
-    uint32_t *keep = at<uint32_t>(L, L->cp.keep), *kscan = at<uint32_t>(L, L->cp.kscan);
+    const unsigned nb = (unsigned)((n + 1 + PRUNE_TILE - 1) / PRUNE_TILE);   // workgroups of PRUNE_TILE entries, the sentinel entry n included
+    uint64_t *blk_tie = at<uint64_t>(L, L->cp.tie64), *blk_tie_off = at<uint64_t>(L, L->cp.trank);
+    uint32_t *blk_keep = at<uint32_t>(L, L->cp.keep), *blk_keep_off = at<uint32_t>(L, L->cp.f0);   // the sampler's flags: not yet in use
+    uint32_t *kscan = at<uint32_t>(L, L->cp.kscan);
     char *temp = at<char>(L, L->cp.temp);
-    hipLaunchKernelGGL(tie_flag_kernel, dim3(nblk(n + 1)), dim3(TB), 0, s, L->val, n, mode, L->sel, tie);
-    SL_HIP(L, scan_excl<uint64_t>(temp, L->cp.temp_bytes, tie, trank, (size_t)n + 1, s));
-    hipLaunchKernelGGL(keep_flag_kernel, dim3(nblk(n + 1)), dim3(TB), 0, s, L->val, n, mode, L->sel, trank, keep);
-    SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, keep, kscan, (size_t)n + 1, s));
-    hipLaunchKernelGGL(compact_kernel, dim3(nblk(n)), dim3(TB), 0, s, n, keep, kscan, L->colidx, L->val, L->vel,
-                       at<int>(L, L->cp.s_col), at<float>(L, L->cp.s_val), at<float>(L, L->cp.s_vel));
+    hipLaunchKernelGGL(tie_count_kernel, dim3(nb), dim3(TB), 0, s, L->val, n, mode, L->sel, blk_tie);
+    SL_HIP(L, scan_excl<uint64_t>(temp, L->cp.temp_bytes, blk_tie, blk_tie_off, (size_t)nb, s));
+    hipLaunchKernelGGL(keep_count_kernel, dim3(nb), dim3(TB), 0, s, L->val, n, mode, L->sel, blk_tie_off, blk_keep);
+    SL_HIP(L, scan_excl<uint32_t>(temp, L->cp.temp_bytes, blk_keep, blk_keep_off, (size_t)nb, s));
+    hipLaunchKernelGGL(compact_block_kernel, dim3(nb), dim3(TB), 0, s, L->val, n, mode, L->sel, blk_tie_off, blk_keep_off,
+                       L->colidx, L->vel, kscan, at<int>(L, L->cp.s_col), at<float>(L, L->cp.s_val), at<float>(L, L->cp.s_vel));
     hipLaunchKernelGGL(survivor_rowptr_kernel, dim3(nblk(n_out + 1)), dim3(TB), 0, s, n_out, L->rowptr, kscan,
                        at<int>(L, L->cp.rowptr_s));
     // the survivor count is checked at the sampler's read-back
