@@ -562,107 +562,155 @@ __global__ void merge_rowptr_kernel(int n_rows, uint32_t n_in, const int *rowptr
     rowptr[r] = rowptr_s[r] + (int)lower_bound_u64(new_p, k, (uint64_t)r * n_in);
 }
 // The new CSR is written front to back, eight consecutive slots per thread, so that every array is stored once in
-// whole cache lines.  A thread finds the row of its first slot by a search among the few rows that its tile of
-// MERGE_TILE slots touches (merge_tile_rows_kernel finds them); inside the row the survivors and the new connections
-// are both ascending by column, and the slot's rank in their union says how many of each precede it (a bisection).
-// From there the thread walks: the next slot takes the smaller of the next survivor and the next new connection,
-// and both cursors run on through the following rows, whose entries follow in the same two arrays.
+// whole cache lines.  Inside a row the survivors and the new connections are both ascending by column, and a slot's
+// rank in their union says how many of each precede it (a bisection).  merge_tile_kernel does that for the first slot
+// of every tile of MERGE_TILE slots, which fixes the runs of survivors and of new connections that the tile consumes;
+// the tile's workgroup copies exactly those runs into LDS (coalesced), each thread bisects for its own first slot and
+// then walks: the next slot takes the smaller of the next survivor and the next new connection, and both cursors run
+// on through the following rows, whose entries follow in the same two arrays.
 // The merge also leaves (row, weight, velocity) of every slot packed in 16 bytes for the rebuild of the transposed
 // view, which then needs one 16-byte gather per connection, and (KEYS) the (column, slot) pairs that view is sorted from.
 struct __align__(16) RowValVel { int row; float val; float vel; int pad; };
 constexpr int MERGE_RUN = 8;                    // consecutive slots per thread
 constexpr int MERGE_TILE = MERGE_RUN * TB;      // slots per block
 
-__global__ void merge_tile_rows_kernel(long n_tiles, int n_rows, const int *rowptr, long nnz, int2 *tile_rows)
+// survivors of row j left of the slot of rank m in the row, searched in [a_lo, a_hi]; A(i) / B(i) = column of the
+// row's i-th survivor / i-th new connection
+template <typename FA, typename FB>
+__device__ __forceinline__ int merge_split(int m, int a_lo, int a_hi, FA &&A, FB &&B)
+{
+    while (a_lo < a_hi) {
+        const int mid = (a_lo + a_hi) >> 1;
+        if (A(mid) < B(m - mid - 1)) a_lo = mid + 1; else a_hi = mid;
+    }
+    return a_lo;
+}
+
+// per tile: x, y = first and last row with a slot in the tile; z, w = survivors and new connections consumed by the
+// tiles before it.  Entry n_tiles closes the list with (.., .., ns, k).
+__global__ void merge_tile_kernel(long n_tiles, int n_rows, uint32_t n_in, const int *rowptr_s, const int *rowptr,
+                                  const int *s_col, const uint64_t *new_p, long nnz, long ns, long k, int4 *tile)
 {
     const long b = (long)blockIdx.x * TB + threadIdx.x;
-    if (b >= n_tiles) return;
+    if (b > n_tiles) return;
+    if (b == n_tiles) { tile[b] = make_int4(n_rows - 1, n_rows - 1, (int)ns, (int)k); return; }
     const long first = b * MERGE_TILE, last = min(first + MERGE_TILE, nnz) - 1;
-    tile_rows[b] = make_int2(row_of(rowptr, n_rows, (int)first), row_of(rowptr, n_rows, (int)last));
+    const int j = row_of(rowptr, n_rows, (int)first);
+    const int d0 = rowptr[j], s0 = rowptr_s[j];
+    const int na = rowptr_s[j + 1] - s0, nb = (rowptr[j + 1] - d0) - na;
+    const long t0 = (long)d0 - s0;
+    const int m = (int)(first - d0);
+    const uint64_t base = (uint64_t)j * n_in;
+    const int a = merge_split(m, max(0, m - nb), min(m, na), [&](int i) { return (uint64_t)s_col[s0 + i]; },
+                              [&](int i) { return new_p[t0 + i] - base; });
+    tile[b] = make_int4(j, row_of(rowptr, n_rows, (int)last), s0 + a, (int)(t0 + (m - a)));
 }
 
 template <bool KEYS>
-__global__ __launch_bounds__(TB) void merge_rows_kernel(long nnz, uint32_t n_in, const int2 *tile_rows, const int *rowptr_s,
+__global__ __launch_bounds__(TB) void merge_rows_kernel(long nnz, uint32_t n_in, const int4 *tile, const int *rowptr_s,
                                                         const int *rowptr, const int *s_col, const float *s_val,
                                                         const float *s_vel, const uint64_t *new_p, Rng rng, float limit,
                                                         int *col, float *val, float *vel, RowValVel *packed, uint32_t *key,
                                                         uint32_t *pay)
 {
+    __shared__ int l_col[MERGE_TILE];
+    __shared__ float l_val[MERGE_TILE], l_vel[MERGE_TILE];
+    __shared__ uint64_t l_new[MERGE_TILE];
+    const int4 here = tile[blockIdx.x], next = tile[blockIdx.x + 1];
+    const int SA0 = here.z, TB0 = here.w;
+    const int n_sa = min(next.z - SA0, MERGE_TILE), n_tb = min(next.w - TB0, MERGE_TILE);   // they add up to the tile's slots
+    for (int i = threadIdx.x; i < n_sa; i += TB) {
+        l_col[i] = s_col[SA0 + i];
+        l_val[i] = s_val[SA0 + i];
+        l_vel[i] = s_vel[SA0 + i];
+    }
+    for (int i = threadIdx.x; i < n_tb; i += TB) l_new[i] = new_p[TB0 + i];
+    __syncthreads();
     const long d_first = (long)blockIdx.x * MERGE_TILE + (long)threadIdx.x * MERGE_RUN;
-    if (d_first >= nnz) return;
-    const int2 jr = tile_rows[blockIdx.x];
-    int lo = jr.x, hi = jr.y;                          // the last row that starts at or before the first slot
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (rowptr[mid] <= d_first) lo = mid; else hi = mid - 1;
-    }
-    int j = lo;
-    long sa, tb;                                       // cursors: next survivor, next new connection
-    int s_end, row_end;                                // end of row j in the survivor array and in the new CSR
-    {
-        const int d0 = rowptr[j], s0 = rowptr_s[j];
-        s_end = rowptr_s[j + 1];
-        row_end = rowptr[j + 1];
-        const int na = s_end - s0, nb = (row_end - d0) - na;
-        const long t0 = (long)d0 - s0;
-        const int m = (int)(d_first - d0);             // rank of the first slot in its row
-        const uint64_t base = (uint64_t)j * n_in;
-        int a_lo = max(0, m - nb), a_hi = min(m, na);  // a = survivors among the m connections left of the slot
-        while (a_lo < a_hi) {
-            const int mid = (a_lo + a_hi) >> 1;
-            if ((uint64_t)s_col[s0 + mid] < new_p[t0 + (m - mid - 1)] - base) a_lo = mid + 1; else a_hi = mid;
-        }
-        sa = s0 + a_lo;
-        tb = t0 + (m - a_lo);
-    }
-    const int run = (int)min((long)MERGE_RUN, nnz - d_first);
+    const int run = (int)max(0L, min((long)MERGE_RUN, nnz - d_first));
     int ci[MERGE_RUN], rj[MERGE_RUN];
     float cw[MERGE_RUN], cv[MERGE_RUN];
 #pragma unroll
-    for (int u = 0; u < MERGE_RUN; ++u) {
-        ci[u] = 0; rj[u] = 0; cw[u] = 0.f; cv[u] = 0.f;
-        if (u < run) {
-            while (d_first + u >= row_end) {           // on to the next row that has a slot (empty rows are skipped)
-                ++j;
-                s_end = rowptr_s[j + 1];
-                row_end = rowptr[j + 1];
-            }
-            const long t_end = (long)row_end - s_end;  // end of row j among the new connections
+    for (int u = 0; u < MERGE_RUN; ++u) { ci[u] = 0; rj[u] = 0; cw[u] = 0.f; cv[u] = 0.f; }
+    if (run > 0) {
+        int lo = here.x, hi = here.y;                  // the last row that starts at or before the first slot
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (rowptr[mid] <= d_first) lo = mid; else hi = mid - 1;
+        }
+        int j = lo;
+        int sa, tb;                                    // cursors into the tile's runs: next survivor, next new connection
+        int s_end, row_end;                            // end of row j in the survivor array and in the new CSR
+        {
+            const int d0 = rowptr[j], s0 = rowptr_s[j];
+            s_end = rowptr_s[j + 1];
+            row_end = rowptr[j + 1];
+            const int na = s_end - s0, nb = (row_end - d0) - na;
+            const int t0 = d0 - s0;
+            const int m = (int)(d_first - d0);         // rank of the first slot in its row
             const uint64_t base = (uint64_t)j * n_in;
-            const int ca = sa < s_end ? s_col[sa] : 0;
-            const uint64_t pb = tb < t_end ? new_p[tb] : 0;
-            const bool survivor = sa < s_end && (tb >= t_end || (uint64_t)ca < pb - base);
-            rj[u] = j;
-            if (survivor) { ci[u] = ca; cw[u] = s_val[sa]; cv[u] = s_vel[sa]; ++sa; }
-            else { ci[u] = (int)(pb - base); cw[u] = fresh_weight(rng, pb, limit); ++tb; }
+            // the cursors at this slot lie inside the tile's runs, which bounds the search to what LDS holds
+            const int a_lo = max(max(0, m - nb), max(SA0 - s0, m - (TB0 + n_tb - t0)));
+            const int a_hi = min(min(m, na), min(SA0 + n_sa - s0, m - (TB0 - t0)));
+            const int a = merge_split(m, a_lo, a_hi, [&](int i) { return (uint64_t)l_col[s0 + i - SA0]; },
+                                      [&](int i) { return l_new[t0 + i - TB0] - base; });
+            sa = s0 + a - SA0;
+            tb = t0 + (m - a) - TB0;
+        }
+#pragma unroll
+        for (int u = 0; u < MERGE_RUN; ++u) {
+            if (u < run) {
+                while (d_first + u >= row_end) {       // on to the next row that has a slot (empty rows are skipped)
+                    ++j;
+                    s_end = rowptr_s[j + 1];
+                    row_end = rowptr[j + 1];
+                }
+                const int sa_end = min(s_end - SA0, n_sa);             // end of row j in the tile's run of survivors
+                const int tb_end = min(row_end - s_end - TB0, n_tb);   // and in its run of new connections
+                const uint64_t base = (uint64_t)j * n_in;
+                const int ca = sa < sa_end ? l_col[sa] : 0;
+                const uint64_t pb = tb < tb_end ? l_new[tb] : 0;
+                const bool survivor = sa < sa_end && (tb >= tb_end || (uint64_t)ca < pb - base);
+                rj[u] = j;
+                if (survivor) { ci[u] = ca; cw[u] = l_val[sa]; cv[u] = l_vel[sa]; ++sa; }
+                else { ci[u] = (int)(pb - base); cw[u] = fresh_weight(rng, pb, limit); ++tb; }
+            }
         }
     }
-    if (run == MERGE_RUN) {
+    // The results change hands through LDS (the input runs are no longer needed) so that every store instruction of a
+    // wavefront covers one contiguous kilobyte.
+    __syncthreads();
+    int *l_row = (int *)l_new;
+    {
+        const int o = threadIdx.x * MERGE_RUN;
 #pragma unroll
         for (int h = 0; h < MERGE_RUN; h += 4) {
-            *(int4 *)(col + d_first + h) = make_int4(ci[h], ci[h + 1], ci[h + 2], ci[h + 3]);
-            *(float4 *)(val + d_first + h) = make_float4(cw[h], cw[h + 1], cw[h + 2], cw[h + 3]);
-            *(float4 *)(vel + d_first + h) = make_float4(cv[h], cv[h + 1], cv[h + 2], cv[h + 3]);
-            if (KEYS) {
-                *(uint4 *)(key + d_first + h) = make_uint4(ci[h], ci[h + 1], ci[h + 2], ci[h + 3]);
-                const uint32_t q = (uint32_t)(d_first + h);
-                *(uint4 *)(pay + d_first + h) = make_uint4(q, q + 1, q + 2, q + 3);
-            }
+            *(int4 *)(l_col + o + h) = make_int4(ci[h], ci[h + 1], ci[h + 2], ci[h + 3]);
+            *(float4 *)(l_val + o + h) = make_float4(cw[h], cw[h + 1], cw[h + 2], cw[h + 3]);
+            *(float4 *)(l_vel + o + h) = make_float4(cv[h], cv[h + 1], cv[h + 2], cv[h + 3]);
+            *(int4 *)(l_row + o + h) = make_int4(rj[h], rj[h + 1], rj[h + 2], rj[h + 3]);
         }
-        if (packed) {
-#pragma unroll
-            for (int u = 0; u < MERGE_RUN; ++u) packed[d_first + u] = RowValVel{rj[u], cw[u], cv[u], 0};
-        }
-    } else {
-#pragma unroll
-        for (int u = 0; u < MERGE_RUN; ++u)
-            if (u < run) {
-                const long d = d_first + u;
-                col[d] = ci[u]; val[d] = cw[u]; vel[d] = cv[u];
-                if (packed) packed[d] = RowValVel{rj[u], cw[u], cv[u], 0};
-                if (KEYS) { key[d] = (uint32_t)ci[u]; pay[d] = (uint32_t)d; }
-            }
     }
+    __syncthreads();
+    const long D0 = (long)blockIdx.x * MERGE_TILE;
+    const int cnt = (int)min((long)MERGE_TILE, nnz - D0);
+    for (int i4 = threadIdx.x; 4 * i4 + 3 < cnt; i4 += TB) {
+        const int4 c = *(const int4 *)(l_col + 4 * i4);
+        *(int4 *)(col + D0 + 4 * i4) = c;
+        *(float4 *)(val + D0 + 4 * i4) = *(const float4 *)(l_val + 4 * i4);
+        *(float4 *)(vel + D0 + 4 * i4) = *(const float4 *)(l_vel + 4 * i4);
+        if (KEYS) {
+            *(uint4 *)(key + D0 + 4 * i4) = make_uint4(c.x, c.y, c.z, c.w);
+            const uint32_t q = (uint32_t)(D0 + 4 * i4);
+            *(uint4 *)(pay + D0 + 4 * i4) = make_uint4(q, q + 1, q + 2, q + 3);
+        }
+    }
+    for (int i = (cnt & ~3) + threadIdx.x; i < cnt; i += TB) {
+        col[D0 + i] = l_col[i]; val[D0 + i] = l_val[i]; vel[D0 + i] = l_vel[i];
+        if (KEYS) { key[D0 + i] = (uint32_t)l_col[i]; pay[D0 + i] = (uint32_t)(D0 + i); }
+    }
+    if (packed)
+        for (int i = threadIdx.x; i < cnt; i += TB) packed[D0 + i] = RowValVel{l_row[i], l_val[i], l_vel[i], 0};
 }
 __global__ void pack_rows_kernel(int n_rows, const int *ptr, const float *val, const float *vel, RowValVel *packed)
 {
@@ -1069,15 +1117,16 @@ static int rebuild(sl_layer *L, long ns, long k, uint32_t generation, hipStream_
     const long n = ns + k;
     if (n > 0) {
         const long n_tiles = (n + MERGE_TILE - 1) / MERGE_TILE;
-        int2 *tile_rows = at<int2>(L, L->cp.f0);      // the sampler is done with its flag arrays
-        hipLaunchKernelGGL(merge_tile_rows_kernel, dim3(nblk(n_tiles)), dim3(TB), 0, s, n_tiles, n_out, L->rowptr, n, tile_rows);
+        int4 *tile = at<int4>(L, L->cp.f0);           // the sampler is done with its flag arrays
+        hipLaunchKernelGGL(merge_tile_kernel, dim3(nblk(n_tiles + 1)), dim3(TB), 0, s, n_tiles, n_out, n_in, rowptr_s, L->rowptr,
+                           s_col, new_p, n, ns, k, tile);
         const Rng rng = make_rng(L, generation);
         if (L->has_csc)
-            hipLaunchKernelGGL(merge_rows_kernel<true>, dim3((unsigned)n_tiles), dim3(TB), 0, s, n, n_in, tile_rows, rowptr_s,
+            hipLaunchKernelGGL(merge_rows_kernel<true>, dim3((unsigned)n_tiles), dim3(TB), 0, s, n, n_in, tile, rowptr_s,
                                L->rowptr, s_col, s_val, s_vel, new_p, rng, L->cfg.init_limit, L->colidx, L->val, L->vel,
                                at<RowValVel>(L, L->cp.packed), at<uint32_t>(L, L->cp.keyA), at<uint32_t>(L, L->cp.payA));
         else
-            hipLaunchKernelGGL(merge_rows_kernel<false>, dim3((unsigned)n_tiles), dim3(TB), 0, s, n, n_in, tile_rows, rowptr_s,
+            hipLaunchKernelGGL(merge_rows_kernel<false>, dim3((unsigned)n_tiles), dim3(TB), 0, s, n, n_in, tile, rowptr_s,
                                L->rowptr, s_col, s_val, s_vel, new_p, rng, L->cfg.init_limit, L->colidx, L->val, L->vel,
                                (RowValVel *)nullptr, (uint32_t *)nullptr, (uint32_t *)nullptr);
     }
