@@ -210,22 +210,31 @@ static void launch_select_hist(const float *val, long n, int mode, int shift, Se
 __global__ void select_pick_kernel(SelState *st, int last)
 {
     SelState &s = st[blockIdx.x];
-    __shared__ uint32_t h[256];               // one parallel fetch instead of 256 dependent global loads
-    h[threadIdx.x] = s.hist[threadIdx.x];
+    __shared__ uint32_t inc[2][256];          // running sums of the histogram (256 threads, eight doubling steps)
+    __shared__ int first;
+    const int t = threadIdx.x;
+    const uint32_t mine = s.hist[t];
+    inc[0][t] = mine;
+    if (t == 0) first = 255;
     __syncthreads();
-    if (threadIdx.x == 0 && s.active) {
-        uint32_t cum = 0;
-        int d = 0;
-        for (; d < 255; ++d) {
-            if (cum + h[d] >= s.krem) break;
-            cum += h[d];
-        }
-        s.krem -= cum;
+    int cur = 0;
+    for (int o = 1; o < 256; o <<= 1) {
+        inc[cur ^ 1][t] = inc[cur][t] + (t >= o ? inc[cur][t - o] : 0u);
+        cur ^= 1;
+        __syncthreads();
+    }
+    // the first digit (below 255) whose running sum reaches krem, else digit 255
+    const uint32_t krem = s.krem;
+    if (t < 255 && inc[cur][t] >= krem) atomicMin(&first, t);
+    __syncthreads();
+    const int d = first;
+    __syncthreads();                           // every thread has read krem and first before they change
+    if (t == d && s.active) {
+        s.krem = krem - (inc[cur][t] - mine);  // minus the entries in the digits below d
         s.prefix = (s.prefix << 8) | (uint32_t)d;
         if (last) { s.thresh = s.prefix; s.need = s.krem; }
     }
-    __syncthreads();
-    s.hist[threadIdx.x] = 0;
+    s.hist[t] = 0;
 }
 
 // tie[p] = 1 in the low (class 0) or high (class 1) half iff |val[p]| equals its class threshold
