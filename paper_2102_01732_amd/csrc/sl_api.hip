@@ -416,13 +416,20 @@ int sparse_layers_evolve(sl_layer *const *layers, int32_t count, double zeta, ui
     // waits of one layer (survivor count, accepted candidates, longest row) overlap the kernels of the others.
     std::vector<int> rc((size_t)count, SL_OK);
     std::vector<std::thread> workers;
-    for (int k = 1; k < count; ++k)
-        workers.emplace_back([&, k] {
-            hipError_t e = hipSetDevice(dev);
-            rc[k] = e != hipSuccess ? set_err(layers[k], SL_EHIP, "hipSetDevice: %s", hipGetErrorString(e))
-                                    : sparse_layer_evolve(layers[k], zeta, generation, hip_streams[k]);
-        });
+    std::vector<int> inline_later;   // layers for which no thread could be started: they run on this one
+    for (int k = 1; k < count; ++k) {
+        try {
+            workers.emplace_back([&, k] {
+                hipError_t e = hipSetDevice(dev);
+                rc[k] = e != hipSuccess ? set_err(layers[k], SL_EHIP, "hipSetDevice: %s", hipGetErrorString(e))
+                                        : sparse_layer_evolve(layers[k], zeta, generation, hip_streams[k]);
+            });
+        } catch (...) {
+            inline_later.push_back(k);
+        }
+    }
     rc[0] = sparse_layer_evolve(layers[0], zeta, generation, hip_streams[0]);
+    for (int k : inline_later) rc[k] = sparse_layer_evolve(layers[k], zeta, generation, hip_streams[k]);
     for (auto &w : workers) w.join();
     for (int k = 0; k < count; ++k)
         if (rc[k]) return rc[k];
