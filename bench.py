@@ -77,9 +77,19 @@ def run_small(name, torch, np, binding, wl, dev, with_cpu):
     # one step = a forward launch per layer (+ the fix-up of the split output layer), the loss, a backward launch
     # per layer and one update launch: these small networks are bound by the latency between dependent launches
     launches = 2 * len(w.layers) + 3
+    # the bytes one step would move if every connection fetched its own operand row (forward, backward, update of
+    # every layer); the operands of these networks fit an L2, so this is an upper bound of what crosses the fabric
+    step_bytes = 0
+    for li, spec in enumerate(w.layers):
+        step_bytes += byte_counts("forward_spmm", spec, B, li > 0)[1]
+        step_bytes += byte_counts("backward_fused" if li > 0 else "sddmm", spec, B, li > 0)[1]
+        step_bytes += byte_counts("update", spec, B, li > 0)[1]
+    ms_step = dt / nb * 1e3
     rec = dict(workload=name, dims=list(w.dims), steps=nb, value=w.n_samples / dt, unit="samples/s",
-               ms_per_step=dt / nb * 1e3, includes="one epoch + one SET evolution", launches_per_step=launches,
-               us_per_launch=dt / nb * 1e6 / launches, bound="latency between dependent kernel launches")
+               ms_per_step=ms_step, includes="one epoch + one SET evolution", launches_per_step=launches,
+               us_per_launch=dt / nb * 1e6 / launches, bound="latency between dependent kernel launches",
+               gather_model_bytes_per_step=step_bytes, gather_model_gbs=step_bytes / ms_step / 1e6,
+               gather_model_frac=step_bytes / ms_step / 1e6 / HBM_PEAK_GBS)
     net.close()
     if with_cpu:
         from oracle import oracle as orc
