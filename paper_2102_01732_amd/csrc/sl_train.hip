@@ -627,13 +627,13 @@ __global__ __launch_bounds__(BLOCK) void bwd_pair_kernel(BwdArgs a)
 // Span kernel for the forward pass of matrices whose rows are very short (mean <= 3 entries: the
 // epsilon = 1 layers).  The backward kernels keep one row per group: their span variants were measured
 // slower, twice over (four held rows, four accumulators and the per-entry row selection cost 120 registers
-// and half the occupancy: 0.50 instead of 0.28 ms on the 10^6 -> 2 layer).  A group owns R = 4 CONSECUTIVE rows and walks their
-// entries as one stream in chunks of 8, so eight row gathers are in flight whatever the individual
-// row lengths are and no gather slot is padding.  Which of the four rows an entry belongs to follows
-// from the five row pointers held in registers; each row's accumulator takes the entry with a weight
+// and half the occupancy: 0.50 instead of 0.28 ms on the 10^6 -> 2 layer).  A group owns R = 2 CONSECUTIVE rows
+// (measured against 3, 4 and 8: 4-5 % faster at every batch size) and walks their entries as one stream in chunks
+// of 8, so that the gathers of both rows are in flight together.  Which of the rows an entry belongs to follows
+// from the R + 1 row pointers held in registers; each row's accumulator takes the entry with a weight
 // that is zero for the other rows.  Same arithmetic per row, in the same order, as the row kernels.
 // ------------------------------------------------------------------------------------------------
-static constexpr int SPAN_R = 4;
+static constexpr int SPAN_R = 2;
 static constexpr int SPAN_U = 8;
 
 template <int G>
