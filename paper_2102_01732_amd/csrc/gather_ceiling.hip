@@ -334,6 +334,7 @@ int main()
     const long total = 8L << 30;   // 8 GiB gathered per launch
     run<32>({4096L, 8192L, 16384L, 65536L, 262144L, 1048576L, 4194304L}, total);
     run<8>({65536L, 262144L, 1048576L}, total / 4);
+    run<4>({32768L, 65536L, 131072L}, total / 8);   // 64-byte rows: half a cache line
     run<64>({65536L, 262144L, 1048576L}, total);
     run_walk();
     run_walk_sync();
