@@ -1,7 +1,7 @@
 """Writes tests/golden/set_mlp_1m_step.json: digests and sampled values of ONE evolution, of the
-first training step and of the states after FOUR and after SIXTEEN training steps of the
-one-million-neuron workload, computed by the CPU oracle alone (about half an hour on one core, a
-few minutes on eight).  Nothing from the GPU path is read or stored.
+first training step and of the states after FOUR, after SIXTEEN and after all 128 training steps of
+an epoch of the one-million-neuron workload, computed by the CPU oracle alone (about an hour on
+eight cores).  Nothing from the GPU path is read or stored.
 
     python tests/golden/make_1m_golden.py
 """
@@ -22,6 +22,7 @@ ROW_SAMPLES = 48       # sampled neurons per layer (full batch rows are stored)
 VAL_STRIDE = 8192      # every VAL_STRIDE-th stored connection
 STEPS = 4              # training steps (minibatches 0..3) behind the "after_steps" values
 MORE_STEPS = 16        # ... and behind the "after_more_steps" values
+EPOCH_STEPS = 128      # ... and behind the "after_epoch" values (the whole epoch of the workload)
 
 
 def digest(a):
@@ -36,7 +37,7 @@ def sample_rows(n, layer_id):
 def main():
     w = wl.WORKLOADS["set_mlp_1m"]
     t0 = time.time()
-    X, y = wl.dataset(w, MORE_STEPS * w.batch)
+    X, y = wl.dataset(w, EPOCH_STEPS * w.batch)
     blocks = wl.to_batch_blocks(X, w.batch)
     x0, y_all, y = blocks[0], y, y[: w.batch]
     layers = [orc.OracleLayer(s.n_in, s.n_out, s.nnz, s.act_kind, s.act_parity, w.alpha, s.init_limit, w.lr,
@@ -89,13 +90,15 @@ def main():
             })
         return rec
 
-    for k in range(1, MORE_STEPS):
+    for k in range(1, EPOCH_STEPS):
         losses.append(net.train_step(blocks[k], y_all[k * w.batch:(k + 1) * w.batch]))
         print("step", k + 1, time.time() - t0, flush=True)
         if k + 1 == STEPS:
             out["after_steps"] = {"steps": STEPS, "loss_means": list(losses), "layers": sampled_state()}
-    out["after_more_steps"] = {"steps": MORE_STEPS, "loss_means": list(losses), "layers": sampled_state()}
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "set_mlp_1m_step.json")
+        if k + 1 == MORE_STEPS:
+            out["after_more_steps"] = {"steps": MORE_STEPS, "loss_means": list(losses), "layers": sampled_state()}
+    out["after_epoch"] = {"steps": EPOCH_STEPS, "loss_means": list(losses), "layers": sampled_state()}
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), os.environ.get("GOLDEN_OUT", "set_mlp_1m_step.json"))
     json.dump(out, open(path, "w"))
     print("wrote", path, os.path.getsize(path), "bytes in", time.time() - t0, "s")
 

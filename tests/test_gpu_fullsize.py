@@ -131,11 +131,12 @@ def test_one_million_neuron_four_training_steps(setup):
     net.close()
 
 
-def test_one_million_neuron_sixteen_training_steps(setup):
-    """Sixteen steps of the loop that bench.py times, against the oracle's state after the same sixteen steps."""
+def steps_against_the_golden_state(setup, key):
     import torch
     binding, golden, w = setup
-    after = golden["after_more_steps"]
+    if key not in golden:
+        pytest.skip(f"tests/golden/set_mlp_1m_step.json has no {key!r} block (re-run make_1m_golden.py)")
+    after = golden[key]
     steps, B = after["steps"], w.batch
     X, y = wl.dataset(w, steps * B)
     blocks = torch.from_numpy(wl.to_batch_blocks(X, B)).cuda()
@@ -146,6 +147,8 @@ def test_one_million_neuron_sixteen_training_steps(setup):
         net.loss_sum.zero_()
         net.train_step(blocks[k], yd[k * B:(k + 1) * B], B)
         losses.append(net.loss_sum.item() / B)
+    worst = max(abs(got - ref) / abs(ref) for got, ref in zip(losses, after["loss_means"]))
+    print(f"{steps} steps: largest relative difference of a minibatch loss {worst:.3e}", flush=True)
     for k, (got, ref) in enumerate(zip(losses, after["loss_means"])):
         assert abs(got - ref) <= 1e-3 * abs(ref), f"loss of step {k + 1}: {got} vs {ref}"
     stride = golden["val_stride"]
@@ -156,6 +159,17 @@ def test_one_million_neuron_sixteen_training_steps(setup):
         near(vel[idx], g["vel"], g["vel_absmax"], 1e-3, f"layer {li} velocities after {steps} steps")
         near(bias[np.asarray(s1["step"]["rows"])], g["bias"], g["bias_absmax"], 1e-3, f"layer {li} biases after {steps} steps")
     net.close()
+
+
+def test_one_million_neuron_sixteen_training_steps(setup):
+    """Sixteen steps of the loop that bench.py times, against the oracle's state after the same sixteen steps."""
+    steps_against_the_golden_state(setup, "after_more_steps")
+
+
+def test_one_million_neuron_whole_epoch(setup):
+    """All 128 minibatches of the epoch that bench.py times, the GPU training on its own, against the oracle's state
+    after the same epoch: every minibatch loss and the sampled weights, velocities and biases at 1e-3."""
+    steps_against_the_golden_state(setup, "after_epoch")
 
 
 LIVE_STEPS = 4
