@@ -4,6 +4,11 @@ an epoch of the one-million-neuron workload, computed by the CPU oracle alone (a
 eight cores).  Nothing from the GPU path is read or stored.
 
     python tests/golden/make_1m_golden.py
+    python tests/golden/make_1m_golden.py --perturbed    # adds "after_epoch_perturbed" to the stored file (another hour)
+
+--perturbed repeats the epoch with the oracle alone from initial weights of which a seeded random half was moved by
+one unit in the last place, and stores the same samples: how far two evaluations of the method that differ only
+by rounding are apart after 128 minibatches of this workload.
 """
 import hashlib
 import json
@@ -103,5 +108,40 @@ def main():
     print("wrote", path, os.path.getsize(path), "bytes in", time.time() - t0, "s")
 
 
+def perturbed():
+    w = wl.WORKLOADS["set_mlp_1m"]
+    t0 = time.time()
+    X, y = wl.dataset(w, EPOCH_STEPS * w.batch)
+    blocks = wl.to_batch_blocks(X, w.batch)
+    layers = [orc.OracleLayer(s.n_in, s.n_out, s.nnz, s.act_kind, s.act_parity, w.alpha, s.init_limit, w.lr,
+                              w.momentum, 0.0, w.seed, s.layer_id) for s in w.layers]
+    rng = np.random.Generator(np.random.PCG64(20210201))
+    for L in layers:                       # one unit in the last place, up, on a random half of the weights
+        val = L.val.copy()
+        pick = rng.random(L.nnz) < 0.5
+        val[pick] = np.nextafter(val[pick], np.float32(np.inf))
+        L.set_state(L.rowptr, L.colidx, val, L.vel, L.bias, L.bias_vel)
+    net = orc.OracleMLP(layers)
+    losses = []
+    for k in range(EPOCH_STEPS):
+        losses.append(net.train_step(blocks[k], y[k * w.batch:(k + 1) * w.batch]))
+        print("perturbed step", k + 1, time.time() - t0, flush=True)
+    rec = []
+    for li, L in enumerate(layers):
+        rows = sample_rows(L.n_out, li)
+        idx = np.arange(0, L.nnz, VAL_STRIDE)
+        rec.append({"val": L.val[idx].astype(np.float64).tolist(), "vel": L.vel[idx].astype(np.float64).tolist(),
+                    "bias": L.bias[rows].astype(np.float64).tolist()})
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "set_mlp_1m_step.json")
+    out = json.load(open(path))
+    out["after_epoch_perturbed"] = {"steps": EPOCH_STEPS, "loss_means": losses, "layers": rec,
+                                    "perturbation": "a seeded random half of the initial weights of every layer moved up by one unit in the last place"}
+    json.dump(out, open(path, "w"))
+    print("added after_epoch_perturbed to", path, "in", time.time() - t0, "s")
+
+
 if __name__ == "__main__":
-    main()
+    if "--perturbed" in sys.argv[1:]:
+        perturbed()
+    else:
+        main()
