@@ -3,7 +3,8 @@ bench.py times (B = 128, all four layers on one GPU), against digests and sample
 tests/golden/make_1m_golden.py computed with the CPU oracle alone.  Topology, indices and fresh
 weights are compared bit for bit over ALL entries (sha256); fp32 tensors on sampled neurons and
 every 8192nd connection, within 1e-4 of the tensor's largest oracle magnitude after the first step and
-within 1e-3 after four and after sixteen steps.
+within 1e-3 after four and after sixteen steps; after the whole epoch of 128 steps against the distance between
+two roundings of the oracle itself (see test_one_million_neuron_whole_epoch).
 
 The last tests run the oracle itself at full size next to the GPU (it shares its rows among the host's cores;
 results do not depend on the thread count): four minibatches, each from the ORACLE's state, with every
@@ -176,6 +177,35 @@ def steps_against_the_golden_state(setup, key, strict=True):
 def test_one_million_neuron_sixteen_training_steps(setup):
     """Sixteen steps of the loop that bench.py times, against the oracle's state after the same sixteen steps."""
     steps_against_the_golden_state(setup, "after_more_steps")
+
+
+def test_one_million_neuron_whole_epoch(setup):
+    """All 128 minibatches of the epoch that bench.py times, the GPU training on its own, against the oracle's own
+    epoch.  This workload does not damp differences: its loss climbs from 0.85 into the thousands, and the ORACLE
+    ITSELF, restarted from initial weights of which half were moved by one unit in the last place, ends the epoch
+    4-5 % away from its first run in the velocities, 3e-4 .. 9e-4 in the weights and up to 1.1 % in single
+    minibatch losses (block "after_epoch_perturbed" of the golden file, written by the oracle alone).  A 1e-3
+    bound on every tensor after the epoch is therefore not a property that any second evaluation of the method
+    has here; what is asserted is that the GPU is no farther from the oracle than that second rounding of the
+    oracle is (twice its normwise distance, per tensor), that the first 64 minibatch losses agree to 1e-3 and all
+    of them to twice the perturbed run's largest difference, and that the epoch's mean loss agrees to 1e-3."""
+    binding, golden, w = setup
+    if "after_epoch_perturbed" not in golden:
+        pytest.skip("tests/golden/set_mlp_1m_step.json has no 'after_epoch_perturbed' block (make_1m_golden.py --perturbed)")
+    ref, other = golden["after_epoch"], golden["after_epoch_perturbed"]
+    losses, dist = steps_against_the_golden_state(setup, "after_epoch", strict=False)
+    l_ref, l_other = np.asarray(ref["loss_means"]), np.asarray(other["loss_means"])
+    rel = np.abs(np.asarray(losses) - l_ref) / np.abs(l_ref)
+    rel_other = np.abs(l_other - l_ref) / np.abs(l_ref)
+    assert rel[:64].max() <= 1e-3, f"loss of step {int(rel[:64].argmax()) + 1} differs by {rel[:64].max():.3e}"
+    assert rel.max() <= 2 * rel_other.max(), (rel.max(), rel_other.max())
+    assert abs(np.mean(losses) - l_ref.mean()) <= 1e-3 * l_ref.mean()
+    for li, (a, b) in enumerate(zip(ref["layers"], other["layers"])):
+        for what in ("val", "vel", "bias"):
+            r, q = np.asarray(a[what]), np.asarray(b[what])
+            own = np.linalg.norm(r - q) / np.linalg.norm(r)      # the oracle against its perturbed self
+            print(f"layer {li} {what}: GPU - oracle {dist[(li, what)][1]:.3e}, perturbed oracle - oracle {own:.3e}", flush=True)
+            assert dist[(li, what)][1] <= 2 * own + 1e-4, f"layer {li} {what}: {dist[(li, what)][1]:.3e} vs {own:.3e}"
 
 
 LIVE_STEPS = 4
